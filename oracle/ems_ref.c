@@ -1,0 +1,400 @@
+/*
+ * ems_ref.c -- CPU oracle for the EMS prefill compression path (arXiv 2412.08521).
+ *
+ * TEST INFRASTRUCTURE ONLY (see ems_ref.h).  Plain loops, fp64 throughout, no tiling,
+ * no fusion: every function takes the steps of the paper in the paper's order so that
+ * it can be checked against the text by eye.  OpenMP only spreads independent rows /
+ * heads over cores.
+ */
+#include "ems_ref.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define REF_OK 0
+#define REF_BAD (-1)
+
+static int score_params_ok(const ems_ref_params* p)
+{
+    if (!p) return 0;
+    if (p->batch < 1 || p->q_heads < 1 || p->kv_heads < 1 || p->head_dim < 1) return 0;
+    if (p->q_heads % p->kv_heads) return 0;
+    if (p->seq_len < 1 || p->window < 1 || p->window > p->seq_len) return 0;
+    return 1;
+}
+
+static int full_params_ok(const ems_ref_params* p)
+{
+    if (!score_params_ok(p)) return 0;
+    if (!(p->window < p->budget && p->budget <= p->seq_len)) return 0;
+    if (p->pool_kernel < 1 || (p->pool_kernel % 2) == 0) return 0;
+    if (!(p->merge_ratio >= 0.0)) return 0;
+    return 1;
+}
+
+int ems_ref_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Sec. 4.2: N_budget = N_imp + L_win ; gamma = (N_budget + N_tbm) / N_budget, so with
+ * r = gamma - 1 the to-be-merged set holds floor(r * N_budget) tokens, limited by the
+ * number of candidates that are neither local nor important. */
+int ems_ref_sizes(const ems_ref_params* p, int32_t* n_imp, int32_t* n_tbm)
+{
+    if (!full_params_ok(p)) return REF_BAD;
+    int32_t imp = p->budget - p->window;
+    double want = floor(p->merge_ratio * (double)p->budget);
+    int32_t room = p->seq_len - p->budget; /* = N - W - N_imp */
+    int32_t tbm = want > (double)room ? room : (int32_t)want;
+    if (n_imp) *n_imp = imp;
+    if (n_tbm) *n_tbm = tbm;
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Sec. 3.2.  A is the N x N causal attention weight matrix of one q-head:
+ *   A[i][j] = softmax_j( q_i . k_j / sqrt(D) ), j <= i        (Eq. 1 gives the scale)
+ *   s_Glo = sum over all rows i of A[i][:]
+ *   s_Loc = sum over the last L_win rows of A[i][:]
+ * With grouped-query attention the q-heads of a group are added into their kv-head.
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_score(const ems_ref_params* p, const float* q, const float* k,
+                  double* s_glo, double* s_loc, double* lse_opt)
+{
+    if (!score_params_ok(p) || !q || !k || !s_glo || !s_loc) return REF_BAD;
+    const long B = p->batch, Hq = p->q_heads, Hkv = p->kv_heads, D = p->head_dim;
+    const long N = p->seq_len, W = p->window, G = Hq / Hkv;
+    const double scale = p->softmax_scale > 0.0 ? p->softmax_scale : 1.0 / sqrt((double)D);
+
+    memset(s_glo, 0, sizeof(double) * (size_t)(B * Hkv * N));
+    memset(s_loc, 0, sizeof(double) * (size_t)(B * Hkv * N));
+
+    const int T = ems_ref_threads();
+    double* part = (double*)malloc(sizeof(double) * (size_t)T * 2 * (size_t)N);
+    double* rows = (double*)malloc(sizeof(double) * (size_t)T * (size_t)N);
+    double* kd = (double*)malloc(sizeof(double) * (size_t)(N * D));
+    if (!part || !rows || !kd) { free(part); free(rows); free(kd); return REF_BAD; }
+
+    for (long b = 0; b < B; ++b) {
+        for (long h = 0; h < Hq; ++h) {
+            const long kv = h / G;
+            const float* Qh = q + ((b * Hq + h) * N) * D;
+            const float* Kh = k + ((b * Hkv + kv) * N) * D;
+            double* glo = s_glo + (b * Hkv + kv) * N;
+            double* loc = s_loc + (b * Hkv + kv) * N;
+            double* lse = lse_opt ? lse_opt + (b * Hq + h) * N : NULL;
+            for (long t = 0; t < N * D; ++t) kd[t] = (double)Kh[t];
+            memset(part, 0, sizeof(double) * (size_t)T * 2 * (size_t)N);
+
+#pragma omp parallel num_threads(T)
+            {
+#ifdef _OPENMP
+                const int tid = omp_get_thread_num();
+#else
+                const int tid = 0;
+#endif
+                double* a = rows + (size_t)tid * (size_t)N;
+                double* pg = part + (size_t)tid * 2 * (size_t)N;
+                double* pl = pg + N;
+                double qd[1024];
+                double* qbuf = D <= 1024 ? qd : (double*)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(static, 1)
+                for (long i = 0; i < N; ++i) {
+                    for (long d = 0; d < D; ++d) qbuf[d] = (double)Qh[i * D + d];
+                    double m = -INFINITY;
+                    for (long j = 0; j <= i; ++j) {
+                        const double* kj = kd + j * D;
+                        double acc = 0.0;
+#pragma omp simd reduction(+ : acc)
+                        for (long d = 0; d < D; ++d) acc += qbuf[d] * kj[d];
+                        a[j] = acc * scale;
+                        if (a[j] > m) m = a[j];
+                    }
+                    double sum = 0.0;
+                    for (long j = 0; j <= i; ++j) { a[j] = exp(a[j] - m); sum += a[j]; }
+                    const int local_row = (i >= N - W);
+                    for (long j = 0; j <= i; ++j) {
+                        const double w = a[j] / sum;
+                        pg[j] += w;
+                        if (local_row) pl[j] += w;
+                    }
+                    if (lse) lse[i] = m + log(sum);
+                }
+                if (qbuf != qd) free(qbuf);
+            }
+            /* fixed-order reduction over threads */
+            for (int t = 0; t < T; ++t) {
+                const double* pg = part + (size_t)t * 2 * (size_t)N;
+                const double* pl = pg + N;
+                for (long j = 0; j < N; ++j) { glo[j] += pg[j]; loc[j] += pl[j]; }
+            }
+        }
+    }
+    free(part); free(rows); free(kd);
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Eq. 2: s = max( s_Glo * (sum(s_Loc)/N) / (sum(s_Glo)/N) , s_Loc ) element-wise,
+ * then the mean pooling of Sec. 4.2 (stride 1, same length, zero padding, divisor
+ * always the kernel width).
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_combine_pool(const ems_ref_params* p, const double* s_glo,
+                         const double* s_loc, double* s_out)
+{
+    if (!score_params_ok(p) || !s_glo || !s_loc || !s_out) return REF_BAD;
+    if (p->pool_kernel < 1 || (p->pool_kernel % 2) == 0) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len;
+    const long half = (p->pool_kernel - 1) / 2;
+    double* s = (double*)malloc(sizeof(double) * (size_t)N);
+    if (!s) return REF_BAD;
+    for (long u = 0; u < BH; ++u) {
+        const double* glo = s_glo + u * N;
+        const double* loc = s_loc + u * N;
+        double sum_glo = 0.0, sum_loc = 0.0;
+        for (long j = 0; j < N; ++j) { sum_glo += glo[j]; sum_loc += loc[j]; }
+        const double align = (sum_loc / (double)N) / (sum_glo / (double)N);
+        for (long j = 0; j < N; ++j) {
+            const double g = glo[j] * align;
+            s[j] = g > loc[j] ? g : loc[j];
+        }
+        for (long j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (long t = -half; t <= half; ++t) {
+                const long jj = j + t;
+                if (jj >= 0 && jj < N) acc += s[jj];
+            }
+            s_out[u * N + j] = acc / (double)p->pool_kernel;
+        }
+    }
+    free(s);
+    return REF_OK;
+}
+
+typedef struct { double score; int32_t pos; } ranked_t;
+
+/* higher score first; equal scores: lower position first */
+static int by_rank(const void* x, const void* y)
+{
+    const ranked_t* a = (const ranked_t*)x;
+    const ranked_t* b = (const ranked_t*)y;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    return (a->pos > b->pos) - (a->pos < b->pos);
+}
+
+static int by_pos(const void* x, const void* y)
+{
+    const int32_t a = *(const int32_t*)x, b = *(const int32_t*)y;
+    return (a > b) - (a < b);
+}
+
+/* ------------------------------------------------------------------------------------
+ * Sec. 4.2, token partition.  The last L_win tokens are local and always kept; the
+ * others are ranked by score: the first N_imp are the important tokens (class
+ * centres), the next N_tbm the to-be-merged tokens, the rest irrelevant (evicted).
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_partition(const ems_ref_params* p, const double* s_pooled,
+                      int32_t* imp_idx, int32_t* tbm_idx)
+{
+    int32_t n_imp, n_tbm;
+    if (ems_ref_sizes(p, &n_imp, &n_tbm) != REF_OK || !s_pooled || !imp_idx) return REF_BAD;
+    if (n_tbm > 0 && !tbm_idx) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len;
+    const long cand = N - p->window;
+    ranked_t* r = (ranked_t*)malloc(sizeof(ranked_t) * (size_t)(cand > 0 ? cand : 1));
+    if (!r) return REF_BAD;
+    for (long u = 0; u < BH; ++u) {
+        for (long j = 0; j < cand; ++j) { r[j].score = s_pooled[u * N + j]; r[j].pos = (int32_t)j; }
+        qsort(r, (size_t)cand, sizeof(ranked_t), by_rank);
+        for (long t = 0; t < n_imp; ++t) imp_idx[u * n_imp + t] = r[t].pos;
+        for (long t = 0; t < n_tbm; ++t) tbm_idx[u * n_tbm + t] = r[n_imp + t].pos;
+        qsort(imp_idx + u * n_imp, (size_t)n_imp, sizeof(int32_t), by_pos);
+        if (n_tbm > 0) qsort(tbm_idx + u * n_tbm, (size_t)n_tbm, sizeof(int32_t), by_pos);
+    }
+    free(r);
+    return REF_OK;
+}
+
+int ems_ref_select(const ems_ref_params* p, const double* s_glo, const double* s_loc,
+                   double* s_pooled_opt, int32_t* imp_idx, int32_t* tbm_idx)
+{
+    if (!full_params_ok(p)) return REF_BAD;
+    const size_t n = (size_t)p->batch * p->kv_heads * p->seq_len;
+    double* s = s_pooled_opt ? s_pooled_opt : (double*)malloc(sizeof(double) * n);
+    if (!s) return REF_BAD;
+    int rc = ems_ref_combine_pool(p, s_glo, s_loc, s);
+    if (rc == REF_OK) rc = ems_ref_partition(p, s, imp_idx, tbm_idx);
+    if (!s_pooled_opt) free(s);
+    return rc;
+}
+
+static double l2norm(const float* x, long D)
+{
+    double acc = 0.0;
+    for (long d = 0; d < D; ++d) acc += (double)x[d] * (double)x[d];
+    return sqrt(acc);
+}
+
+/* ------------------------------------------------------------------------------------
+ * Eq. 5: d_i = argmax_d R[i][d] over the class centres, with R the cosine similarity of
+ * the keys; tokens whose best similarity does not exceed tau go to the zero class
+ * (Sec. 4.2).  A key of norm 0 has similarity 0 to everything.
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_dest(const ems_ref_params* p, const float* k,
+                 const int32_t* imp_idx, const int32_t* tbm_idx,
+                 int32_t* tbm_dest, double* tbm_sim, double* k_norm_opt)
+{
+    int32_t n_imp, n_tbm;
+    if (ems_ref_sizes(p, &n_imp, &n_tbm) != REF_OK || !k || !imp_idx) return REF_BAD;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest || !tbm_sim)) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len, D = p->head_dim;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < BH; ++u) {
+        const float* Ku = k + u * N * D;
+        const int32_t* imp = imp_idx + u * n_imp;
+        const int32_t* tbm = tbm_idx ? tbm_idx + u * n_tbm : NULL;
+        double* cn = (double*)malloc(sizeof(double) * (size_t)n_imp);
+        if (!cn) { bad = 1; continue; }
+        for (long c = 0; c < n_imp; ++c) {
+            cn[c] = l2norm(Ku + (long)imp[c] * D, D);
+            if (k_norm_opt) k_norm_opt[u * (n_imp + n_tbm) + c] = cn[c];
+        }
+        for (long i = 0; i < n_tbm; ++i) {
+            const float* ki = Ku + (long)tbm[i] * D;
+            const double ni = l2norm(ki, D);
+            if (k_norm_opt) k_norm_opt[u * (n_imp + n_tbm) + n_imp + i] = ni;
+            double best = -INFINITY;
+            int32_t arg = 0;
+            for (long c = 0; c < n_imp; ++c) {
+                const float* kc = Ku + (long)imp[c] * D;
+                double sim = 0.0;
+                if (ni > 0.0 && cn[c] > 0.0) {
+                    for (long d = 0; d < D; ++d)
+                        sim += ((double)ki[d] / ni) * ((double)kc[d] / cn[c]);
+                }
+                if (sim > best) { best = sim; arg = (int32_t)c; }
+            }
+            tbm_sim[u * n_tbm + i] = best;
+            tbm_dest[u * n_tbm + i] = best > p->tau ? arg : p->budget;
+        }
+        free(cn);
+    }
+    return bad ? REF_BAD : REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Sec. 4.2 / App. A: N_tbm + N_imp tokens share N_imp entries, plus one zero-class
+ * entry that collects the evicted ones.  Members of an entry = its centre and the TBM
+ * tokens sent to it.  Values: arithmetic mean of the members.  Keys: only normalised
+ * keys are merged and the norm is kept apart, so the entry's direction is the mean of
+ * the members' unit keys and the stored row is that direction times the centre's own
+ * norm.  The zero-class row keeps the plain means (scale 1).  An entry nobody joined
+ * is the centre itself, copied.  Rows N_imp..budget-1 are the local tokens.
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_merge(const ems_ref_params* p, const float* k, const float* v,
+                  const int32_t* imp_idx, const int32_t* tbm_idx,
+                  const int32_t* tbm_dest,
+                  double* k_out, double* v_out, int32_t* kept_pos, int32_t* slot_count)
+{
+    int32_t n_imp, n_tbm;
+    if (ems_ref_sizes(p, &n_imp, &n_tbm) != REF_OK) return REF_BAD;
+    if (!k || !v || !imp_idx || !k_out || !v_out || !kept_pos || !slot_count) return REF_BAD;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest)) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len, D = p->head_dim;
+    const long Nb = p->budget, W = p->window, rows = Nb + 1;
+    int bad = 0;
+    for (long u = 0; u < BH; ++u) {
+        for (long i = 0; i < n_tbm; ++i) {
+            const int32_t d = tbm_dest[u * n_tbm + i];
+            if (!((d >= 0 && d < n_imp) || d == Nb)) bad = 1;
+        }
+    }
+    if (bad) return REF_BAD;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < BH; ++u) {
+        const float* Ku = k + u * N * D;
+        const float* Vu = v + u * N * D;
+        const int32_t* imp = imp_idx + u * n_imp;
+        const int32_t* tbm = tbm_idx ? tbm_idx + u * n_tbm : NULL;
+        const int32_t* dst = tbm_dest ? tbm_dest + u * n_tbm : NULL;
+        double* Ko = k_out + u * rows * D;
+        double* Vo = v_out + u * rows * D;
+        int32_t* cnt = slot_count + u * (n_imp + 1);
+        int32_t* kp = kept_pos + u * Nb;
+
+        for (long s = 0; s <= n_imp; ++s) {
+            const int zero_class = (s == n_imp);
+            const long row = zero_class ? Nb : s;
+            double* ko = Ko + row * D;
+            double* vo = Vo + row * D;
+            for (long d = 0; d < D; ++d) { ko[d] = 0.0; vo[d] = 0.0; }
+            long members = 0;
+            double centre_norm = 1.0;
+            if (!zero_class) {
+                const float* kc = Ku + (long)imp[s] * D;
+                const float* vc = Vu + (long)imp[s] * D;
+                centre_norm = l2norm(kc, D);
+                for (long d = 0; d < D; ++d) {
+                    ko[d] += centre_norm > 0.0 ? (double)kc[d] / centre_norm : 0.0;
+                    vo[d] += (double)vc[d];
+                }
+                members = 1;
+            }
+            for (long i = 0; i < n_tbm; ++i) {
+                if (dst[i] != (zero_class ? Nb : s)) continue;
+                const float* ki = Ku + (long)tbm[i] * D;
+                const float* vi = Vu + (long)tbm[i] * D;
+                const double ni = l2norm(ki, D);
+                for (long d = 0; d < D; ++d) {
+                    ko[d] += ni > 0.0 ? (double)ki[d] / ni : 0.0;
+                    vo[d] += (double)vi[d];
+                }
+                ++members;
+            }
+            cnt[s] = (int32_t)members;
+            if (!zero_class && members == 1) {
+                const float* kc = Ku + (long)imp[s] * D;
+                const float* vc = Vu + (long)imp[s] * D;
+                for (long d = 0; d < D; ++d) { ko[d] = (double)kc[d]; vo[d] = (double)vc[d]; }
+            } else if (members > 0) {
+                for (long d = 0; d < D; ++d) {
+                    ko[d] = centre_norm * (ko[d] / (double)members);
+                    vo[d] = vo[d] / (double)members;
+                }
+            }
+        }
+        for (long s = 0; s < n_imp; ++s) kp[s] = imp[s];
+        for (long t = 0; t < W; ++t) {
+            const long pos = N - W + t;
+            kp[n_imp + t] = (int32_t)pos;
+            for (long d = 0; d < D; ++d) {
+                Ko[(n_imp + t) * D + d] = (double)Ku[pos * D + d];
+                Vo[(n_imp + t) * D + d] = (double)Vu[pos * D + d];
+            }
+        }
+    }
+    return REF_OK;
+}
+
+int ems_ref_evict_merge(const ems_ref_params* p, const float* k, const float* v,
+                        const int32_t* imp_idx, const int32_t* tbm_idx,
+                        double* k_out, double* v_out, int32_t* kept_pos,
+                        int32_t* tbm_dest, double* tbm_sim, double* k_norm_opt,
+                        int32_t* slot_count)
+{
+    int rc = ems_ref_dest(p, k, imp_idx, tbm_idx, tbm_dest, tbm_sim, k_norm_opt);
+    if (rc != REF_OK) return rc;
+    return ems_ref_merge(p, k, v, imp_idx, tbm_idx, tbm_dest, k_out, v_out, kept_pos, slot_count);
+}
