@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the EMS prefill compression path on one MI355X.
+
+A "step" is one pass of the whole hot path -- Global/Local score, select, evict-then-merge --
+over one layer's synthetic Q/K/V (already resident in HBM) of the named workload.  Prints ONE
+JSON line: compressed tokens/s per layer, per-stage times, the roofline figures of the
+dominant kernel (the key-stationary score pass) and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama3_8b_32k] [--tau 0.6]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_F32_MFMA_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_32k")
+    ap.add_argument("--tau", type=float, default=0.6)
+    ap.add_argument("--f32", action="store_true", help="validation mode (f32 MFMA)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layer", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU by design (every step is independent per "
+                 "(batch, kv-head)); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import ems_inputs
+    from paper_2412_08521_amd import binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = ems_inputs.WORKLOADS[args.workload]
+    mode = B.EMS_F32 if args.f32 else B.EMS_BF16
+    p = B.EmsParams(w.batch, w.q_heads, w.kv_heads, w.head_dim, w.seq_len, w.window, w.budget,
+                    merge_ratio=w.merge_ratio, tau=args.tau, pool_kernel=w.pool_kernel, dtype=mode)
+    n_imp, n_tbm = B.ems_partition_sizes(p)
+
+    # ---- synthetic inputs, generated on the host per batch entry and moved to HBM
+    t0 = time.time()
+    tdt = p.torch_dtype
+    q = torch.empty((w.batch, w.q_heads, w.seq_len, w.head_dim), dtype=tdt, device="cuda")
+    k = torch.empty((w.batch, w.kv_heads, w.seq_len, w.head_dim), dtype=tdt, device="cuda")
+    v = torch.empty_like(k)
+    sample = None
+    for b in range(w.batch):
+        inp = ems_inputs.generate(w, layer=args.layer, batch_slice=slice(b, b + 1))
+        for name, dst in (("q", q), ("k", k), ("v", v)):
+            bits = getattr(inp, name)
+            if mode == B.EMS_F32:
+                dst[b].copy_(torch.from_numpy(ems_inputs.bf16_bits_to_f32(bits[0])))
+            else:
+                dst[b].copy_(torch.from_numpy(bits[0].view(np.int16)).view(torch.bfloat16))
+        if b == 0:
+            G = w.q_heads // w.kv_heads
+            sample = (inp.f32("q")[:, :G].copy(), inp.f32("k")[:, :1].copy(), inp.f32("v")[:, :1].copy())
+        log(f"generated batch entry {b} ({time.time() - t0:.1f}s)")
+        del inp
+
+    # ---- everything the timed region touches is allocated up front
+    ws_bytes = B.ems_workspace_bytes(p)
+    ws_score = torch.empty(ws_bytes[0], dtype=torch.uint8, device="cuda")
+    ws_select = torch.empty(ws_bytes[1], dtype=torch.uint8, device="cuda")
+    ws_merge = torch.empty(ws_bytes[2], dtype=torch.uint8, device="cuda")
+    s_glo = torch.empty((w.batch, w.kv_heads, w.seq_len), dtype=torch.float32, device="cuda")
+    s_loc = torch.empty_like(s_glo)
+    imp = torch.empty((w.batch, w.kv_heads, n_imp), dtype=torch.int32, device="cuda")
+    tbm = torch.empty((w.batch, w.kv_heads, n_tbm), dtype=torch.int32, device="cuda")
+    outs = B.alloc_evict_merge_outputs(p, "cuda")
+    lse = torch.empty((w.batch, w.q_heads, w.seq_len), dtype=torch.float32, device="cuda")
+
+    def score():
+        B.ems_global_local_score(p, q, k, ws=ws_score, out=(s_glo, s_loc))
+
+    def select():
+        B.ems_select(p, s_glo, s_loc, ws=ws_select, out=(imp, tbm))
+
+    def merge():
+        B.ems_evict_merge(p, k, v, imp, tbm, ws=ws_merge, out=outs)
+
+    def step():
+        score(); select(); merge()
+
+    def timed(fn, reps):
+        """Average milliseconds per call over `reps` back-to-back calls (HIP events on the
+        stream the kernels are launched on)."""
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b_.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b_) / reps
+
+    for i in range(args.warmup):
+        step()
+        torch.cuda.synchronize()
+        log(f"warmup {i} done")
+    ms_step = timed(step, args.steps)
+    log(f"timed {args.steps} steps: {ms_step:.3f} ms/step")
+
+    K = args.steps
+    stages = {"score": timed(score, K), "select": timed(select, K), "evict_merge": timed(merge, K)}
+    ms_pass1 = timed(lambda: B.ems_attention_lse(p, q, k, ws=ws_score, out=lse), K)
+    ms_pass2 = timed(lambda: B.ems_global_local_score_from_lse(p, q, k, lse, ws=ws_score,
+                                                               out=(s_glo, s_loc)), K)
+    log(f"stages ms: {stages}; pass1 {ms_pass1:.3f} pass2 {ms_pass2:.3f}")
+
+    # ---- roofline of the dominant kernel: algorithmic flops = causal pairs only
+    pairs = w.seq_len * (w.seq_len + 1) // 2
+    flops_pass = 2.0 * w.head_dim * pairs * w.q_heads * w.batch
+    peak = PEAK_F32_MFMA_TFLOPS if args.f32 else PEAK_BF16_TFLOPS
+    achieved = flops_pass / (ms_pass2 * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_score_pass2_{w.name}.json")
+    if os.path.exists(tpath) and not args.f32:
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    roofline = {"bound": "mfma", "kernel": "score_pass2_kernel", "achieved": round(achieved, 2),
+                "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": traffic, "flops_per_launch": flops_pass,
+                "ms_per_launch": round(ms_pass2, 4)}
+    pass1 = {"kernel": "score_pass1_kernel", "achieved": round(flops_pass / (ms_pass1 * 1e-3) / 1e12, 2),
+             "unit": "TFLOP/s", "frac": round(flops_pass / (ms_pass1 * 1e-3) / 1e12 / peak, 4),
+             "ms_per_launch": round(ms_pass1, 4)}
+
+    tokens = w.batch * w.seq_len
+    result = {
+        "metric": "compressed tokens/s per layer (score+evict+merge)",
+        "value": round(tokens / (ms_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if args.f32 else "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads,
+                   "kv_heads": w.kv_heads, "head_dim": w.head_dim, "seq_len": w.seq_len,
+                   "window": w.window, "budget": w.budget, "merge_ratio": w.merge_ratio,
+                   "tau": args.tau, "pool_kernel": w.pool_kernel, "layer": args.layer},
+        "stages_us": {k_: round(v_ * 1e3, 1) for k_, v_ in stages.items()},
+        "roofline": roofline, "score_pass1": pass1,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        from oracle import ems_ref
+        qs, ks, vs = sample
+        G = w.q_heads // w.kv_heads
+        rp = ems_ref.RefParams(1, G, 1, w.head_dim, w.seq_len, w.window, budget=w.budget,
+                               merge_ratio=w.merge_ratio, tau=args.tau, pool_kernel=w.pool_kernel)
+        t0 = time.time()
+        o_glo, o_loc = ems_ref.score(rp, qs, ks)
+        t_score = time.time() - t0
+        t0 = time.time()
+        _, o_imp, o_tbm = ems_ref.select(rp, o_glo, o_loc)
+        ems_ref.evict_merge(rp, ks, vs, o_imp, o_tbm)
+        t_rest = time.time() - t0
+        t_layer = (t_score + t_rest) * w.batch * w.kv_heads
+        result["cpu_baseline"] = {
+            "value": round(tokens / t_layer, 2), "unit": "tokens/s", "cores": ems_ref.threads(),
+            "kind": "oracle",
+            "sample": (f"one of the {w.batch * w.kv_heads} (batch, kv-head) units at full length "
+                       f"N={w.seq_len}: batch 0, kv-head 0 with its {G} q-heads (score "
+                       f"{t_score:.2f}s, select+evict_merge {t_rest:.3f}s); layer time = unit "
+                       f"time x {w.batch * w.kv_heads} (units are independent and cost the same)"),
+        }
+        log(f"cpu baseline: score {t_score:.2f}s rest {t_rest:.3f}s")
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,171 @@
+/*
+ * ems.h -- C ABI of the MI355X (gfx950) implementation of the EMS prefill compression
+ * path (arXiv 2412.08521, "EMS: Adaptive Evict-then-Merge Strategy for Head-wise KV Cache
+ * Compression Based on Global-Local Importance").
+ *
+ * One transformer layer's Q/K/V go in; a per-head Global-Local importance score, a token
+ * partition and an equal-size compressed K/V cache come out.  Three calls, in order:
+ *
+ *     ems_global_local_score  ->  ems_select  ->  ems_evict_merge
+ *
+ * Conventions shared by every entry point
+ *   - Every tensor pointer is a DEVICE pointer, contiguous and row-major, owned by the
+ *     caller.  The library never allocates, frees or synchronises: work is enqueued on
+ *     the caller's stream (`hip_stream` is a hipStream_t, NULL = the default stream) and
+ *     scratch space comes in through `ws` (sizes from ems_workspace_bytes; 256-byte
+ *     aligned).  Outputs are fully overwritten.
+ *   - Layouts (Appendix A, "Two-Levels of Parallelism": (batch, heads, len, head_dim)):
+ *         q        [B, Hq , N, D]      k, v     [B, Hkv, N, D]
+ *     in `dtype` (bf16 or f32).  q-head h attends kv-head h / (Hq/Hkv).
+ *   - Return value: an ems_status.  Argument errors are found on the host before any
+ *     launch; nothing is enqueued when a call fails with an argument error.
+ *   - Calls that use the same workspace on different streams at once race.
+ *
+ * Derived sizes (Sec. 4.2): N_imp = budget - window class centres, N_tbm =
+ * min(floor(merge_ratio * budget), N - budget) to-be-merged tokens, i.e. the paper's
+ * merge magnification gamma = 1 + merge_ratio.  ems_partition_sizes returns them.
+ */
+#ifndef EMS_H
+#define EMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EMS_OK = 0,
+    EMS_ERR_INVALID_ARG = -1,  /* null pointer, inconsistent or out-of-range sizes */
+    EMS_ERR_UNSUPPORTED = -2,  /* valid in principle, not built (e.g. head_dim) */
+    EMS_ERR_WORKSPACE = -3,    /* ws is null, misaligned or smaller than required */
+    EMS_ERR_LAUNCH = -4        /* the HIP runtime refused a launch */
+} ems_status;
+
+typedef enum {
+    EMS_BF16 = 0,  /* bf16 I/O, bf16 MFMA with f32 accumulation */
+    EMS_F32 = 1    /* f32 I/O, f32 MFMA: the validation mode */
+} ems_dtype;
+
+typedef struct {
+    int32_t batch;         /* B  >= 1 */
+    int32_t q_heads;       /* Hq >= 1 */
+    int32_t kv_heads;      /* Hkv >= 1, divides Hq (grouped-query attention) */
+    int32_t head_dim;      /* D in {64, 128} */
+    int32_t seq_len;       /* N  >= 1 */
+    int32_t window;        /* L_win: 1 <= window <= N; (< budget for select/evict_merge) */
+    int32_t budget;        /* N_budget: window < budget <= N */
+    float   merge_ratio;   /* r >= 0 : N_tbm = floor(r * budget), clamped to N - budget */
+    float   tau;           /* merge iff cosine similarity > tau (paper: about 0.6) */
+    int32_t pool_kernel;   /* odd >= 1 (<= 63) mean-pool width, 1 = off (paper: 7) */
+    float   softmax_scale; /* <= 0 means 1/sqrt(D) (Eq. 1) */
+    int32_t dtype;         /* ems_dtype of q, k, v, k_out, v_out */
+} ems_params;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int ems_version(void);
+
+/* Static, human-readable text for an ems_status. */
+const char* ems_strerror(int status);
+
+/* Sec. 4.2 sizes: N_imp and N_tbm for these parameters (host only). */
+int ems_partition_sizes(const ems_params* p, int32_t* n_imp, int32_t* n_tbm);
+
+/* Bytes of device scratch each call needs for these parameters (host only; any of the
+ * three outputs may be NULL). */
+int ems_workspace_bytes(const ems_params* p, size_t* score_ws, size_t* select_ws,
+                        size_t* merge_ws);
+
+/*
+ * Global and Local accumulated attention scores (Sec. 3.2; Eq. 1 gives the logits).
+ * With A^h the N x N causal softmax attention matrix of q-head h (logits q_i.k_j * scale,
+ * j <= i), per kv-head:
+ *     s_glo[j] = sum_{h in group} sum_{i}            A^h[i][j]
+ *     s_loc[j] = sum_{h in group} sum_{i >= N - window} A^h[i][j]
+ * The N x N matrix is never stored: a first pass finds each row's log-sum-exp, a second
+ * pass re-forms the weights tile by tile and adds them column-wise (App. A, "Global-Local
+ * Score Efficiency Discussion").
+ *   q, k      in : device, layouts above, `dtype`
+ *   s_glo     out: device [B, Hkv, N] f32
+ *   s_loc     out: device [B, Hkv, N] f32
+ *   lse_opt   out: device [B, Hq, N] f32 natural-log row log-sum-exp, or NULL
+ *   ws        device scratch of at least score_ws bytes
+ * Uses batch, q_heads, kv_heads, head_dim, seq_len, window, softmax_scale, dtype.
+ */
+int ems_global_local_score(const ems_params* p, const void* q, const void* k,
+                           float* s_glo, float* s_loc, float* lse_opt,
+                           void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * The two halves of ems_global_local_score as separate calls, for callers whose attention
+ * kernel already produced the row log-sum-exp: the paper's own kernel re-uses that
+ * "lse" of the forward pass and only re-forms the weights (App. A, "Global-Local Score
+ * Efficiency Discussion").
+ *   ems_attention_lse: lse[b][h][i] = ln sum_{j<=i} exp(q_i.k_j * scale), device
+ *       [B, Hq, N] f32 (first pass only).
+ *   ems_global_local_score_from_lse: s_glo / s_loc from q, k and such an lse (second pass
+ *       only); with lse from ems_attention_lse the result equals ems_global_local_score
+ *       up to the rounding of one ln/log2 conversion.
+ * Workspace: score_ws bytes, as for ems_global_local_score.
+ */
+int ems_attention_lse(const ems_params* p, const void* q, const void* k, float* lse,
+                      void* ws, size_t ws_bytes, void* hip_stream);
+int ems_global_local_score_from_lse(const ems_params* p, const void* q, const void* k,
+                                    const float* lse, float* s_glo, float* s_loc,
+                                    void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Global-Local score (Eq. 2), mean pooling and token partition (Sec. 4.2).
+ *     s[j]  = max( s_glo[j] * (sum(s_loc)/N) / (sum(s_glo)/N), s_loc[j] )
+ *     s~[j] = (1/pool_kernel) * sum_{|t| <= (pool_kernel-1)/2} s[j+t]   (zeros outside)
+ * The last `window` positions are local tokens and are not ranked.  Of the others, the
+ * N_imp highest-scoring are the important tokens (class centres) and the next N_tbm the
+ * to-be-merged tokens; equal scores rank by lower position first.
+ *   s_glo, s_loc in : device [B, Hkv, N] f32
+ *   s_gl_opt     out: device [B, Hkv, N] f32 pooled score s~ (all N positions), or NULL
+ *   imp_idx      out: device [B, Hkv, N_imp] i32 positions, ascending
+ *   tbm_idx      out: device [B, Hkv, N_tbm] i32 positions, ascending (may be NULL iff
+ *                     N_tbm == 0)
+ *   ws           device scratch of at least select_ws bytes
+ */
+int ems_select(const ems_params* p, const float* s_glo, const float* s_loc,
+               float* s_gl_opt, int32_t* imp_idx, int32_t* tbm_idx,
+               void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Head-wise evict-then-merge (Sec. 4.2, Eq. 5, App. A).  For every to-be-merged token i
+ * the destination is d_i = argmax_c cos(k_i, k_c) over the class centres c (lowest slot on
+ * ties); it merges into d_i if that similarity exceeds tau, else into the zero class
+ * (eviction).  Every slot then holds the average of its members (the centre and the
+ * tokens merged into it): values as a plain mean; keys as the mean of the members' unit
+ * keys times the centre's own norm (the zero-class row keeps scale 1).  A slot nobody
+ * joined is a bit-exact copy of its centre.  Rows N_imp..budget-1 are the `window` local
+ * tokens, copied.  Every head therefore emits exactly `budget` cache rows plus one
+ * zero-class row.
+ *   k, v       in : device, layouts above, `dtype`
+ *   imp_idx    in : device [B, Hkv, N_imp] i32, ascending, values in [0, N - window)
+ *   tbm_idx    in : device [B, Hkv, N_tbm] i32 (NULL iff N_tbm == 0)
+ *   k_out,v_out out: device [B, Hkv, budget + 1, D] `dtype`; row `budget` = zero class
+ *                    (mean value / mean unit key of the evicted tokens, zeros if none)
+ *   kept_pos   out: device [B, Hkv, budget] i32 source position of every cache row
+ *   tbm_dest   out: device [B, Hkv, N_tbm] i32 slot in [0, N_imp) or `budget` (zero class)
+ *   tbm_sim    out: device [B, Hkv, N_tbm] f32 winning cosine similarity
+ *   k_norm_opt out: device [B, Hkv, N_imp + N_tbm] f32 key norms of centres, then of TBM
+ *                    tokens, or NULL
+ *   slot_count out: device [B, Hkv, N_imp + 1] i32 members per slot (last = zero class)
+ *   ws         device scratch of at least merge_ws bytes
+ * The index inputs are device data and cannot be checked on the host; positions outside
+ * [0, N) are clamped into range by the kernels rather than dereferenced.
+ */
+int ems_evict_merge(const ems_params* p, const void* k, const void* v,
+                    const int32_t* imp_idx, const int32_t* tbm_idx,
+                    void* k_out, void* v_out, int32_t* kept_pos,
+                    int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
+                    int32_t* slot_count,
+                    void* ws, size_t ws_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMS_H */

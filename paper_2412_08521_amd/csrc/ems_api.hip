@@ -1,0 +1,262 @@
+// Host side of the C ABI declared in include/ems.h: argument validation, workspace
+// carving and kernel launches.  Nothing here allocates, frees or synchronises.
+#include "../../include/ems.h"
+#include "ems_kernels.h"
+
+#include <cmath>
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool score_params_ok(const ems_params* p, int* why)
+{
+    *why = EMS_ERR_INVALID_ARG;
+    if (!p) return false;
+    if (p->batch < 1 || p->q_heads < 1 || p->kv_heads < 1) return false;
+    if (p->q_heads % p->kv_heads) return false;
+    if (p->seq_len < 1 || p->window < 1 || p->window > p->seq_len) return false;
+    if (p->dtype != EMS_BF16 && p->dtype != EMS_F32) return false;
+    if (p->head_dim < 1) return false;
+    if (std::isnan(p->softmax_scale) || std::isinf(p->softmax_scale)) return false;
+    *why = EMS_ERR_UNSUPPORTED;
+    if (p->head_dim != 64 && p->head_dim != 128) return false;
+    if (p->seq_len > (1 << 22)) return false;                       // 32-bit index headroom
+    if ((long long)p->batch * p->kv_heads > 65535) return false;    // grid.y
+    if ((long long)p->batch * p->q_heads * ((p->seq_len + 127) / 128) > (1ll << 30)) return false;
+    return true;
+}
+
+bool full_params_ok(const ems_params* p, int* why)
+{
+    if (!score_params_ok(p, why)) return false;
+    *why = EMS_ERR_INVALID_ARG;
+    if (!(p->window < p->budget && p->budget <= p->seq_len)) return false;
+    if (p->pool_kernel < 1 || p->pool_kernel > 63 || (p->pool_kernel % 2) == 0) return false;
+    if (!(p->merge_ratio >= 0.f) || std::isinf(p->merge_ratio)) return false;
+    if (std::isnan(p->tau)) return false;
+    return true;
+}
+
+void partition_sizes(const ems_params* p, int* n_imp, int* n_tbm)
+{
+    // Sec. 4.2: N_budget = N_imp + L_win, gamma = (N_budget + N_tbm) / N_budget = 1 + r
+    *n_imp = p->budget - p->window;
+    const double want = std::floor((double)p->merge_ratio * (double)p->budget);
+    const int room = p->seq_len - p->budget;
+    *n_tbm = want > (double)room ? room : (int)want;
+}
+
+struct ScorePlan {
+    int n_chunks, chunk_rows, loc_chunk0;
+    size_t off_lse2, off_part_glo, off_part_loc, total;
+};
+
+// Row chunks of the key-stationary pass: small enough that there are a few thousand
+// (key tile, row chunk) work items to balance over 256 compute units, large enough that
+// the keys a block holds in registers are reused over many rows.
+ScorePlan plan_score(const ems_params* p)
+{
+    ScorePlan s{};
+    const int N = p->seq_len;
+    const long long bkv = (long long)p->batch * p->kv_heads;
+    const int kpb = ems::score_keys_per_block(p->dtype == EMS_F32);
+    const int n_key_tiles = (N + kpb - 1) / kpb;
+    auto items = [&](int R) {
+        const int nI = (N + R - 1) / R;
+        long long t = 0;
+        for (int J = 0; J < n_key_tiles; ++J) t += nI - (int)(((long long)J * kpb) / R);
+        return t * bkv;
+    };
+    int R = 4096;
+    while (R > 512 && items(R) < 2048) R >>= 1;
+    s.chunk_rows = R;
+    s.n_chunks = (N + R - 1) / R;
+    s.loc_chunk0 = (N - p->window) / R;
+    size_t off = 0;
+    s.off_lse2 = off; off += align_up(sizeof(float) * (size_t)p->batch * p->q_heads * N);
+    s.off_part_glo = off;
+    s.off_part_loc = off;
+    if (s.n_chunks > 1) {
+        off += align_up(sizeof(float) * (size_t)bkv * s.n_chunks * N);
+        s.off_part_loc = off;
+        off += align_up(sizeof(float) * (size_t)bkv * (s.n_chunks - s.loc_chunk0) * N);
+    }
+    s.total = off;
+    return s;
+}
+
+size_t select_ws_bytes(const ems_params* p)
+{
+    return align_up(sizeof(float) * (size_t)p->batch * p->kv_heads * p->seq_len);
+}
+
+size_t merge_ws_bytes(const ems_params* p)
+{
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+    return align_up(sizeof(float) * (size_t)p->batch * p->kv_heads * (size_t)(n_imp + n_tbm));
+}
+
+bool ws_ok(const void* ws, size_t have, size_t need)
+{
+    return ws && ((uintptr_t)ws % kAlign) == 0 && have >= need;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ems_version(void) { return 100; }
+
+const char* ems_strerror(int status)
+{
+    switch (status) {
+        case EMS_OK: return "ok";
+        case EMS_ERR_INVALID_ARG: return "invalid argument";
+        case EMS_ERR_UNSUPPORTED: return "unsupported configuration";
+        case EMS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case EMS_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int ems_partition_sizes(const ems_params* p, int32_t* n_imp, int32_t* n_tbm)
+{
+    int why;
+    if (!full_params_ok(p, &why)) return why;
+    int a, b;
+    partition_sizes(p, &a, &b);
+    if (n_imp) *n_imp = a;
+    if (n_tbm) *n_tbm = b;
+    return EMS_OK;
+}
+
+int ems_workspace_bytes(const ems_params* p, size_t* score_ws, size_t* select_ws, size_t* merge_ws)
+{
+    int why;
+    if (!score_params_ok(p, &why)) return why;
+    if (score_ws) *score_ws = plan_score(p).total;
+    if (select_ws || merge_ws) {
+        if (!full_params_ok(p, &why)) return why;
+        if (select_ws) *select_ws = select_ws_bytes(p);
+        if (merge_ws) *merge_ws = merge_ws_bytes(p);
+    }
+    return EMS_OK;
+}
+
+static void fill_score_args(ems::ScoreArgs& a, const ems_params* p, const ScorePlan& plan, void* ws)
+{
+    char* w = static_cast<char*>(ws);
+    a.lse2 = w ? reinterpret_cast<float*>(w + plan.off_lse2) : nullptr;
+    a.part_glo = w ? reinterpret_cast<float*>(w + plan.off_part_glo) : nullptr;
+    a.part_loc = w ? reinterpret_cast<float*>(w + plan.off_part_loc) : nullptr;
+    a.batch = p->batch; a.q_heads = p->q_heads; a.kv_heads = p->kv_heads;
+    a.head_dim = p->head_dim; a.seq_len = p->seq_len; a.window = p->window;
+    a.n_chunks = plan.n_chunks; a.chunk_rows = plan.chunk_rows; a.loc_chunk0 = plan.loc_chunk0;
+    const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale
+                                                : 1.0 / std::sqrt((double)p->head_dim);   // Eq. 1
+    a.scale_log2e = (float)(scale * 1.4426950408889634074);
+}
+
+int ems_global_local_score(const ems_params* p, const void* q, const void* k,
+                           float* s_glo, float* s_loc, float* lse_opt,
+                           void* ws, size_t ws_bytes, void* hip_stream)
+{
+    int why;
+    if (!score_params_ok(p, &why)) return why;
+    if (!q || !k || !s_glo || !s_loc) return EMS_ERR_INVALID_ARG;
+    const ScorePlan plan = plan_score(p);
+    if (!ws_ok(ws, ws_bytes, plan.total)) return EMS_ERR_WORKSPACE;
+
+    ems::ScoreArgs a{};
+    a.q = q; a.k = k; a.s_glo = s_glo; a.s_loc = s_loc; a.lse_opt = lse_opt;
+    fill_score_args(a, p, plan, ws);
+    const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = ems::launch_score_pass1(a, p->dtype == EMS_F32, st);
+    if (e == hipSuccess) e = ems::launch_score_pass2(a, p->dtype == EMS_F32, st);
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
+int ems_attention_lse(const ems_params* p, const void* q, const void* k, float* lse,
+                      void* ws, size_t ws_bytes, void* hip_stream)
+{
+    int why;
+    if (!score_params_ok(p, &why)) return why;
+    if (!q || !k || !lse) return EMS_ERR_INVALID_ARG;
+    const ScorePlan plan = plan_score(p);
+    if (!ws_ok(ws, ws_bytes, plan.total)) return EMS_ERR_WORKSPACE;
+    ems::ScoreArgs a{};
+    a.q = q; a.k = k; a.lse_opt = lse;
+    fill_score_args(a, p, plan, ws);
+    const hipError_t e = ems::launch_score_pass1(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
+int ems_global_local_score_from_lse(const ems_params* p, const void* q, const void* k,
+                                    const float* lse, float* s_glo, float* s_loc,
+                                    void* ws, size_t ws_bytes, void* hip_stream)
+{
+    int why;
+    if (!score_params_ok(p, &why)) return why;
+    if (!q || !k || !lse || !s_glo || !s_loc) return EMS_ERR_INVALID_ARG;
+    const ScorePlan plan = plan_score(p);
+    if (!ws_ok(ws, ws_bytes, plan.total)) return EMS_ERR_WORKSPACE;
+    ems::ScoreArgs a{};
+    a.q = q; a.k = k; a.s_glo = s_glo; a.s_loc = s_loc; a.lse_in_nat = lse;
+    fill_score_args(a, p, plan, ws);
+    const hipError_t e = ems::launch_score_pass2(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
+int ems_select(const ems_params* p, const float* s_glo, const float* s_loc,
+               float* s_gl_opt, int32_t* imp_idx, int32_t* tbm_idx,
+               void* ws, size_t ws_bytes, void* hip_stream)
+{
+    int why;
+    if (!full_params_ok(p, &why)) return why;
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+    if (!s_glo || !s_loc || !imp_idx || (n_tbm > 0 && !tbm_idx)) return EMS_ERR_INVALID_ARG;
+    if (!ws_ok(ws, ws_bytes, select_ws_bytes(p))) return EMS_ERR_WORKSPACE;
+
+    ems::SelectArgs a{};
+    a.s_glo = s_glo; a.s_loc = s_loc; a.s_gl_opt = s_gl_opt;
+    a.pooled = static_cast<float*>(ws);
+    a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
+    a.bkv = p->batch * p->kv_heads; a.seq_len = p->seq_len; a.window = p->window;
+    a.n_imp = n_imp; a.n_tbm = n_tbm; a.pool_kernel = p->pool_kernel;
+    const hipError_t e = ems::launch_select(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
+int ems_evict_merge(const ems_params* p, const void* k, const void* v,
+                    const int32_t* imp_idx, const int32_t* tbm_idx,
+                    void* k_out, void* v_out, int32_t* kept_pos,
+                    int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
+                    int32_t* slot_count,
+                    void* ws, size_t ws_bytes, void* hip_stream)
+{
+    int why;
+    if (!full_params_ok(p, &why)) return why;
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+    if (!k || !v || !imp_idx || !k_out || !v_out || !kept_pos || !slot_count) return EMS_ERR_INVALID_ARG;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest || !tbm_sim)) return EMS_ERR_INVALID_ARG;
+    if (!ws_ok(ws, ws_bytes, merge_ws_bytes(p))) return EMS_ERR_WORKSPACE;
+
+    ems::MergeArgs a{};
+    a.k = k; a.v = v; a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
+    a.k_out = k_out; a.v_out = v_out; a.kept_pos = kept_pos;
+    a.tbm_dest = tbm_dest; a.tbm_sim = tbm_sim;
+    a.k_norm = k_norm_opt ? k_norm_opt : static_cast<float*>(ws);
+    a.slot_count = slot_count;
+    a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len;
+    a.window = p->window; a.budget = p->budget; a.n_imp = n_imp; a.n_tbm = n_tbm;
+    a.tau = p->tau;
+    const hipError_t e = ems::launch_evict_merge(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
+}  // extern "C"

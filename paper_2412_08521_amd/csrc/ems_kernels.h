@@ -1,0 +1,58 @@
+// Internal interface between the host-side C ABI (ems_api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ems {
+
+struct ScoreArgs {
+    const void* q;
+    const void* k;
+    float* s_glo;       // [B*Hkv, N]
+    float* s_loc;       // [B*Hkv, N]
+    float* lse_opt;     // [B*Hq, N] natural log, nullable
+    float* lse2;        // [B*Hq, N] base-2 log-sum-exp of c*S (workspace; pass 1 writes it)
+    const float* lse_in_nat;  // caller's natural-log row log-sum-exp for pass 2, or null
+    float* part_glo;    // [B*Hkv, n_chunks, N] (workspace, n_chunks > 1 only)
+    float* part_loc;    // [B*Hkv, n_chunks - loc_chunk0, N]
+    int batch, q_heads, kv_heads, head_dim, seq_len, window;
+    int n_chunks;       // row chunks of pass 2
+    int chunk_rows;     // rows per chunk (multiple of 64)
+    int loc_chunk0;     // first chunk that holds a last-window row
+    float scale_log2e;  // softmax scale * log2(e)
+};
+
+struct SelectArgs {
+    const float* s_glo;
+    const float* s_loc;
+    float* s_gl_opt;    // nullable
+    float* pooled;      // [B*Hkv, N] workspace (ranking keys)
+    int32_t* imp_idx;
+    int32_t* tbm_idx;
+    int bkv, seq_len, window, n_imp, n_tbm, pool_kernel;
+};
+
+struct MergeArgs {
+    const void* k;
+    const void* v;
+    const int32_t* imp_idx;
+    const int32_t* tbm_idx;
+    void* k_out;
+    void* v_out;
+    int32_t* kept_pos;
+    int32_t* tbm_dest;
+    float* tbm_sim;
+    float* k_norm;      // [B*Hkv, n_imp + n_tbm] (caller's k_norm_opt or workspace)
+    int32_t* slot_count;
+    int bkv, head_dim, seq_len, window, budget, n_imp, n_tbm;
+    float tau;
+};
+
+int score_keys_per_block(int dtype_is_f32);
+hipError_t launch_score_pass1(const ScoreArgs& a, bool f32, hipStream_t st);   // rows' log-sum-exp
+hipError_t launch_score_pass2(const ScoreArgs& a, bool f32, hipStream_t st);   // column sums
+hipError_t launch_select(const SelectArgs& a, hipStream_t st);
+hipError_t launch_evict_merge(const MergeArgs& a, bool f32, hipStream_t st);
+
+}  // namespace ems

@@ -1,0 +1,382 @@
+// Head-wise evict-then-merge (Sec. 4.2, Eq. 5, App. A).
+//
+// dest_kernel   for every to-be-merged (TBM) token: cosine similarity of its key with
+//               every class-centre key as an MFMA contraction of the raw keys, scaled by
+//               the reciprocal norms afterwards, with the row arg-max fused into the
+//               accumulator read-out; similarity not above tau -> zero class.
+// merge_kernel  one wave per output row: a centre slot gathers the TBM tokens sent to it
+//               in ascending order and averages (unit keys scaled by the centre's norm,
+//               raw values); one block per head does the same for the zero class; the
+//               local-window rows are copied.  Every output element has exactly one
+//               writer, so there are no atomics and results are reproducible bit for bit.
+#include "ems_common.h"
+#include "ems_kernels.h"
+
+namespace ems {
+
+constexpr int kMrgWaves = 4;
+constexpr int kMrgBlock = kMrgWaves * kWave;
+
+template <typename T> struct DestCfg { static constexpr int kStageRows = 64; };
+template <> struct DestCfg<float> { static constexpr int kStageRows = 32; };
+
+__device__ __forceinline__ int clamp_pos(int p, int n) { return min(max(p, 0), n - 1); }
+
+// sum of squares of the 16-byte fragment's elements, in f32
+template <typename T> __device__ __forceinline__ float frag_sumsq(const frag_t& f);
+template <> __device__ __forceinline__ float frag_sumsq<bf16_t>(const frag_t& f)
+{
+    const bf16x8_t v = __builtin_bit_cast(bf16x8_t, f);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { const float x = (float)v[i]; s = __builtin_fmaf(x, x, s); }
+    return s;
+}
+template <> __device__ __forceinline__ float frag_sumsq<float>(const frag_t& f)
+{
+    const f32x4_t v = __builtin_bit_cast(f32x4_t, f);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s = __builtin_fmaf(v[i], v[i], s);
+    return s;
+}
+
+__device__ __forceinline__ float inv_norm(float sumsq) { return sumsq > 0.f ? 1.0f / sqrtf(sumsq) : 0.f; }
+
+// ------------------------------------------------------------------------------------
+// Destination of every TBM token (Eq. 5 with key-cosine similarity, then the threshold).
+// Block = (128 TBM tokens, one (b, kv-head)); each wave keeps 32 TBM keys in registers as
+// the MFMA B operand (tokens -> lanes) and the centre keys stream through LDS as the A
+// operand (centres -> accumulator registers), so the running arg-max is a per-lane pair.
+// ------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
+{
+    constexpr int kStageRows = DestCfg<T>::kStageRows;
+    constexpr int kFrags = Tile<T, D>::kFrags;
+    constexpr int kStride = Tile<T, D>::kLdsStride;
+    constexpr int kCpr = Tile<T, D>::kChunksPerRow;
+    constexpr int kPerThread = kCpr * kStageRows / kMrgBlock;
+
+    __shared__ __attribute__((aligned(16))) char lds[kStageRows * kStride];
+    __shared__ __attribute__((aligned(16))) float lds_rn[kStageRows];
+
+    const int N = a.seq_len, n_imp = a.n_imp, n_tbm = a.n_tbm;
+    const int bkv = blockIdx.y;
+    const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
+    const int32_t* imp = a.imp_idx + (size_t)bkv * n_imp;
+    const int32_t* tbm = a.tbm_idx + (size_t)bkv * n_tbm;
+
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int col = lane & 31, half = lane >> 5;
+    const int ti = blockIdx.x * (kMrgWaves * 32) + wave * 32 + col;   // this lane's TBM token
+    const bool t_ok = ti < n_tbm;
+    const int t_pos = t_ok ? clamp_pos(tbm[ti], N) : 0;
+
+    frag_t bt[kFrags];
+    float t_sumsq = 0.f;
+#pragma unroll
+    for (int f = 0; f < kFrags; ++f) {
+        bt[f] = load_frag_or_zero(K, (size_t)t_pos * Tile<T, D>::kRowBytes + f * 32 + half * 16, t_ok);
+        t_sumsq += frag_sumsq<T>(bt[f]);
+    }
+    t_sumsq += __shfl_xor(t_sumsq, 32);
+    const float t_rn = inv_norm(t_sumsq);
+
+    float best = -INFINITY;
+    int arg = 0;
+
+    for (int c0 = 0; c0 < n_imp; c0 += kStageRows) {
+        __syncthreads();                                   // previous tile fully consumed
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int c = threadIdx.x + i * kMrgBlock;
+            const int row = c / kCpr, cc = c % kCpr;
+            const int ci = c0 + row;
+            const bool ok = ci < n_imp;
+            const int pos = ok ? clamp_pos(imp[ci], N) : 0;
+            const frag_t v = load_frag_or_zero(K, ((size_t)pos * kCpr + cc) * 16, ok);
+            *reinterpret_cast<frag_t*>(lds + row * kStride + cc * 16) = v;
+            // the kCpr consecutive lanes that hold one row add up its squares
+            float ss = frag_sumsq<T>(v);
+#pragma unroll
+            for (int o = kCpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+            if (cc == 0) lds_rn[row] = inv_norm(ss);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int rs = 0; rs < kStageRows / 32; ++rs) {
+            const int cbase = c0 + rs * 32;
+            if (cbase >= n_imp) continue;                  // block-uniform
+            f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int f = 0; f < kFrags; ++f) {
+                const frag_t ac = *reinterpret_cast<const frag_t*>(lds + (rs * 32 + col) * kStride + f * 32 + half * 16);
+                mma<T>(acc, ac, bt[f]);
+            }
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4_t rn = *reinterpret_cast<const f32x4_t*>(lds_rn + rs * 32 + 8 * q4 + 4 * half);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ci = cbase + 8 * q4 + 4 * half + e;
+                    const float sim = (acc[4 * q4 + e] * rn[e]) * t_rn;
+                    if (ci < n_imp && sim > best) { best = sim; arg = ci; }
+                }
+            }
+        }
+    }
+    // the other half-wave looked at the other centres of every tile
+    const float best_o = __shfl_xor(best, 32);
+    const int arg_o = __shfl_xor(arg, 32);
+    if (best_o > best || (best_o == best && arg_o < arg)) { best = best_o; arg = arg_o; }
+    if (half == 0 && t_ok) {
+        a.tbm_sim[(size_t)bkv * n_tbm + ti] = best;
+        a.tbm_dest[(size_t)bkv * n_tbm + ti] = best > a.tau ? arg : a.budget;
+        a.k_norm[(size_t)bkv * (n_imp + n_tbm) + n_imp + ti] = sqrtf(t_sumsq);
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Segmented average.  A row of D elements is 16-byte pieces over kLpr lanes, so one wave
+// has kGroups = 64 / kLpr rows in flight per load; members of a slot are dealt to the
+// groups in ascending order and the groups are added by a fixed butterfly at the end.
+// ------------------------------------------------------------------------------------
+template <typename T> struct Pack;
+template <> struct Pack<bf16_t> {
+    static constexpr int kElems = 8;
+    static __device__ __forceinline__ void unpack(const frag_t& f, float (&x)[8])
+    {
+        const bf16x8_t v = __builtin_bit_cast(bf16x8_t, f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = (float)v[i];
+    }
+    static __device__ __forceinline__ frag_t pack(const float (&x)[8])
+    {
+        bf16x8_t v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (bf16_t)x[i];      // round to nearest even
+        return __builtin_bit_cast(frag_t, v);
+    }
+};
+template <> struct Pack<float> {
+    static constexpr int kElems = 4;
+    static __device__ __forceinline__ void unpack(const frag_t& f, float (&x)[4])
+    {
+        const f32x4_t v = __builtin_bit_cast(f32x4_t, f);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = v[i];
+    }
+    static __device__ __forceinline__ frag_t pack(const float (&x)[4])
+    {
+        f32x4_t v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = x[i];
+        return __builtin_bit_cast(frag_t, v);
+    }
+};
+
+template <typename T, int D>
+struct RowAcc {
+    static constexpr int kE = Pack<T>::kElems;
+    static constexpr int kLpr = Tile<T, D>::kChunksPerRow;     // lanes per row
+    static constexpr int kGroups = kWave / kLpr;
+    float k[kE], v[kE];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int i = 0; i < kE; ++i) { k[i] = 0.f; v[i] = 0.f; }
+    }
+    // adds token `pos` (unit key, raw value); returns the key's norm.  All kLpr lanes of
+    // the group must call together.
+    __device__ __forceinline__ float add(const T* K, const T* V, int pos, int piece)
+    {
+        const frag_t fk = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)pos * kLpr + piece) * 16);
+        const frag_t fv = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)pos * kLpr + piece) * 16);
+        float ss = frag_sumsq<T>(fk);
+#pragma unroll
+        for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        const float rn = inv_norm(ss);
+        float xk[kE], xv[kE];
+        Pack<T>::unpack(fk, xk);
+        Pack<T>::unpack(fv, xv);
+#pragma unroll
+        for (int i = 0; i < kE; ++i) { k[i] = __builtin_fmaf(xk[i], rn, k[i]); v[i] += xv[i]; }
+        return sqrtf(ss);
+    }
+    // adds the groups together: afterwards every group holds the total
+    __device__ __forceinline__ void reduce_groups()
+    {
+#pragma unroll
+        for (int o = kLpr; o < kWave; o <<= 1) {
+#pragma unroll
+            for (int i = 0; i < kE; ++i) { k[i] += __shfl_xor(k[i], o); v[i] += __shfl_xor(v[i], o); }
+        }
+    }
+};
+
+// Walks the TBM tokens of chunks `first, first+step, ...` (64 tokens each) whose
+// destination is `target` and adds them to `acc`; returns how many there were.
+template <typename T, int D>
+__device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const MergeArgs& a, const T* K, const T* V,
+                                              const int32_t* tbm, const int32_t* dest, int target,
+                                              int first, int step, int* wlist)
+{
+    constexpr int kLpr = RowAcc<T, D>::kLpr, kGroups = RowAcc<T, D>::kGroups;
+    const int lane = threadIdx.x % kWave;
+    const int grp = lane / kLpr, piece = lane % kLpr;
+    const int n_chunks = (a.n_tbm + kWave - 1) / kWave;
+    int count = 0;
+    for (int ch = first; ch < n_chunks; ch += step) {
+        const int i = ch * kWave + lane;
+        const bool match = i < a.n_tbm && dest[i] == target;
+        const unsigned long long mask = __ballot(match);
+        if (mask == 0ull) continue;                              // wave-uniform
+        const int n = __popcll(mask);
+        if (match) wlist[__popcll(mask & ((1ull << lane) - 1ull))] = clamp_pos(tbm[i], a.seq_len);
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        for (int m0 = 0; m0 < n; m0 += kGroups) {
+            const int m = m0 + grp;
+            if (m < n) acc.add(K, V, wlist[m], piece);
+        }
+        __builtin_amdgcn_wave_barrier();
+        count += n;
+    }
+    return count;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
+{
+    using Acc = RowAcc<T, D>;
+    constexpr int kE = Acc::kE, kLpr = Acc::kLpr;
+
+    __shared__ int wlist_all[kMrgWaves][kWave];
+    __shared__ float zsum[kMrgWaves][2][D];
+    __shared__ int zcnt[kMrgWaves];
+
+    const int N = a.seq_len, W = a.window, Nb = a.budget, n_imp = a.n_imp, n_tbm = a.n_tbm;
+    const int bkv = blockIdx.y;
+    const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
+    const T* V = reinterpret_cast<const T*>(a.v) + ((size_t)bkv * N) * D;
+    T* Ko = reinterpret_cast<T*>(a.k_out) + ((size_t)bkv * (Nb + 1)) * D;
+    T* Vo = reinterpret_cast<T*>(a.v_out) + ((size_t)bkv * (Nb + 1)) * D;
+    const int32_t* imp = a.imp_idx + (size_t)bkv * n_imp;
+    const int32_t* tbm = n_tbm ? a.tbm_idx + (size_t)bkv * n_tbm : nullptr;
+    const int32_t* dest = n_tbm ? a.tbm_dest + (size_t)bkv * n_tbm : nullptr;
+    int32_t* kept = a.kept_pos + (size_t)bkv * Nb;
+    int32_t* cnt = a.slot_count + (size_t)bkv * (n_imp + 1);
+
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int grp = lane / kLpr, piece = lane % kLpr;
+    int* wlist = wlist_all[wave];
+
+    if (blockIdx.x == 0) {
+        // ---- zero class: the four waves split the TBM list, wave 0 adds them in order
+        Acc acc; acc.clear();
+        const int n = gather_members<T, D>(acc, a, K, V, tbm, dest, Nb, wave, kMrgWaves, wlist);
+        acc.reduce_groups();
+        if (grp == 0) {
+#pragma unroll
+            for (int i = 0; i < kE; ++i) { zsum[wave][0][piece * kE + i] = acc.k[i]; zsum[wave][1][piece * kE + i] = acc.v[i]; }
+        }
+        if (lane == 0) zcnt[wave] = n;
+        __syncthreads();
+        if (wave == 0 && grp == 0) {
+            int total = 0;
+            for (int w = 0; w < kMrgWaves; ++w) total += zcnt[w];
+            float ok[kE], ov[kE];
+#pragma unroll
+            for (int i = 0; i < kE; ++i) {
+                float sk = 0.f, sv = 0.f;
+                for (int w = 0; w < kMrgWaves; ++w) { sk += zsum[w][0][piece * kE + i]; sv += zsum[w][1][piece * kE + i]; }
+                const float inv = total > 0 ? 1.0f / (float)total : 0.f;
+                ok[i] = total > 0 ? sk / (float)total : 0.f;
+                ov[i] = total > 0 ? sv / (float)total : 0.f;
+                (void)inv;
+            }
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ok);
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ov);
+            if (lane == 0) cnt[n_imp] = total;
+        }
+        return;
+    }
+
+    const int job = (blockIdx.x - 1) * kMrgWaves + wave;          // wave-uniform
+    if (job >= n_imp + W) return;
+
+    if (job >= n_imp) {
+        // ---- local-window row: copied unchanged
+        const int t = job - n_imp;
+        const int pos = N - W + t;
+        if (grp == 0) {
+            const frag_t fk = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)pos * kLpr + piece) * 16);
+            const frag_t fv = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)pos * kLpr + piece) * 16);
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)job * kLpr + piece) * 16) = fk;
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)job * kLpr + piece) * 16) = fv;
+        }
+        if (lane == 0) kept[job] = pos;
+        return;
+    }
+
+    // ---- class-centre slot
+    const int c_pos = clamp_pos(imp[job], N);
+    Acc acc; acc.clear();
+    float c_norm = 0.f;
+    frag_t raw_k = zero_frag(), raw_v = zero_frag();
+    if (grp == 0) {
+        raw_k = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)c_pos * kLpr + piece) * 16);
+        raw_v = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)c_pos * kLpr + piece) * 16);
+        c_norm = acc.add(K, V, c_pos, piece);
+    }
+    c_norm = __shfl(c_norm, 0);
+    const int members = 1 + gather_members<T, D>(acc, a, K, V, tbm, dest, job, 0, 1, wlist);
+    acc.reduce_groups();
+    if (grp == 0) {
+        frag_t out_k = raw_k, out_v = raw_v;                      // nobody joined: exact copy
+        if (members > 1) {
+            float ok[kE], ov[kE];
+            const float m = (float)members;
+#pragma unroll
+            for (int i = 0; i < kE; ++i) { ok[i] = c_norm * (acc.k[i] / m); ov[i] = acc.v[i] / m; }
+            out_k = Pack<T>::pack(ok);
+            out_v = Pack<T>::pack(ov);
+        }
+        *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)job * kLpr + piece) * 16) = out_k;
+        *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)job * kLpr + piece) * 16) = out_v;
+    }
+    if (lane == 0) {
+        kept[job] = c_pos;
+        cnt[job] = members;
+        a.k_norm[(size_t)bkv * (n_imp + n_tbm) + job] = c_norm;
+    }
+}
+
+template <typename T, int D>
+static hipError_t launch_evict_merge_t(const MergeArgs& a, hipStream_t st)
+{
+    hipError_t e = hipSuccess;
+    if (a.n_tbm > 0) {
+        dim3 g((a.n_tbm + kMrgWaves * 32 - 1) / (kMrgWaves * 32), a.bkv);
+        hipLaunchKernelGGL((dest_kernel<T, D>), g, dim3(kMrgBlock), 0, st, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const int jobs = a.n_imp + a.window;
+    dim3 g(1 + (jobs + kMrgWaves - 1) / kMrgWaves, a.bkv);
+    hipLaunchKernelGGL((merge_kernel<T, D>), g, dim3(kMrgBlock), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_evict_merge(const MergeArgs& a, bool f32, hipStream_t st)
+{
+    if (f32) {
+        if (a.head_dim == 64) return launch_evict_merge_t<float, 64>(a, st);
+        return launch_evict_merge_t<float, 128>(a, st);
+    }
+    if (a.head_dim == 64) return launch_evict_merge_t<bf16_t, 64>(a, st);
+    return launch_evict_merge_t<bf16_t, 128>(a, st);
+}
+
+}  // namespace ems

@@ -1,0 +1,67 @@
+"""Helpers shared by the GPU parity tests: moving generated inputs to the device, the
+tolerance rules, and the band rule for index sets."""
+import numpy as np
+import torch
+
+import ems_inputs
+from oracle.ems_ref import RefParams
+from paper_2412_08521_amd import binding as B
+
+# Stated bars: scores and merged K/V within 2e-2 relative on the bf16 path, 1e-5 in f32 mode.
+RTOL = {B.EMS_BF16: 2e-2, B.EMS_F32: 1e-5}
+
+
+def dev_tensor(bits: np.ndarray, dtype: int) -> torch.Tensor:
+    """bf16 bit patterns (uint16) -> device tensor in the mode's I/O type (exact)."""
+    if dtype == B.EMS_F32:
+        return torch.from_numpy(ems_inputs.bf16_bits_to_f32(bits)).cuda()
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def ref_params(p: B.EmsParams) -> RefParams:
+    return RefParams(p.batch, p.q_heads, p.kv_heads, p.head_dim, p.seq_len, p.window,
+                     budget=p.budget, merge_ratio=p.merge_ratio, tau=p.tau,
+                     pool_kernel=p.pool_kernel, softmax_scale=p.softmax_scale)
+
+
+def rel_err(got, ref, floor_frac=1e-3):
+    """max |got - ref| / max(|ref|, floor), floor = floor_frac * mean|ref| (per call)."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    floor = floor_frac * max(np.abs(ref).mean(), 1e-300)
+    return float((np.abs(got - ref) / np.maximum(np.abs(ref), floor)).max())
+
+
+def assert_rel(got, ref, rtol, what, floor_frac=1e-3):
+    e = rel_err(got, ref, floor_frac)
+    assert e <= rtol, f"{what}: max relative error {e:.3e} > {rtol:.1e}"
+    return e
+
+
+def check_band(idx_imp, idx_tbm, score, n_cand, tol):
+    """Index sets against an oracle score vector with a tolerance band at the two cuts:
+    every candidate whose score is above cut*(1+tol) must be on the upper side, every one
+    below cut*(1-tol) on the lower side; inside the band either side is valid."""
+    s = np.asarray(score, np.float64)[:n_cand]
+    n_imp, n_tbm = len(idx_imp), len(idx_tbm)
+    order = np.sort(s)[::-1]
+    in_imp = np.zeros(n_cand, bool); in_imp[idx_imp] = True
+    in_tbm = np.zeros(n_cand, bool); in_tbm[idx_tbm] = True
+    assert in_imp.sum() == n_imp and in_tbm.sum() == n_tbm and not (in_imp & in_tbm).any()
+    cut1 = order[n_imp - 1]
+    must_imp = s > cut1 * (1 + tol)
+    cannot_imp = s < cut1 * (1 - tol)
+    assert in_imp[must_imp].all(), "a token clearly above the first cut is not important"
+    assert not in_imp[cannot_imp].any(), "a token clearly below the first cut is important"
+    if n_tbm and n_imp + n_tbm < n_cand:
+        cut2 = order[n_imp + n_tbm - 1]
+        kept = in_imp | in_tbm
+        assert kept[s > cut2 * (1 + tol)].all(), "a token clearly above the second cut is evicted"
+        assert not kept[s < cut2 * (1 - tol)].any(), "a token clearly below the second cut is kept"
+    elif n_tbm:
+        assert (in_imp | in_tbm).all()
+
+
+def is_sorted_unique(a):
+    a = np.asarray(a)
+    return bool((np.diff(a) > 0).all())

@@ -1,0 +1,105 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, sizes follow Sec. 4.2, and argument errors are caught before launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2412_08521_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2412_08521_amd import build
+        build.build()
+    return B.lib()
+
+
+def test_exports_match_header(lib):
+    text = open(os.path.join(ROOT, "include", "ems.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ems_[a-z_]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.ems_version() >= 100
+    assert B.strerror(0) == "ok" and "argument" in B.strerror(-1)
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(B.ems_params) == 12 * 4
+    assert [n for n, _ in B.ems_params._fields_] == [
+        "batch", "q_heads", "kv_heads", "head_dim", "seq_len", "window", "budget",
+        "merge_ratio", "tau", "pool_kernel", "softmax_scale", "dtype"]
+
+
+@pytest.mark.parametrize("n,w,nb,r,exp", [(4096, 32, 256, 0.5, (224, 128)),
+                                          (1024, 32, 64, 0.5, (32, 32)),
+                                          (131072, 64, 2048, 0.5, (1984, 1024)),
+                                          (300, 10, 290, 3.0, (280, 10)),
+                                          (100, 10, 20, 0.0, (10, 0))])
+def test_partition_sizes(lib, n, w, nb, r, exp):
+    p = B.EmsParams(1, 8, 2, 128, n, w, nb, merge_ratio=r)
+    assert B.ems_partition_sizes(p) == exp
+
+
+def test_workspace_sizes(lib):
+    p = B.EmsParams(4, 32, 8, 128, 32768, 64, 128)
+    s, t, u = B.ems_workspace_bytes(p)
+    assert s >= 4 * 32 * 32768 * 4 and s % 256 == 0
+    assert t >= 4 * 8 * 32768 * 4 and u >= 4 * 8 * 128 * 4
+
+
+def _bad(**kw):
+    base = dict(batch=1, q_heads=4, kv_heads=2, head_dim=128, seq_len=512, window=16, budget=64)
+    base.update(kw)
+    return B.EmsParams(**base)
+
+
+@pytest.mark.parametrize("p,code", [
+    (_bad(q_heads=3), B.EMS_ERR_INVALID_ARG), (_bad(window=0), B.EMS_ERR_INVALID_ARG),
+    (_bad(window=513), B.EMS_ERR_INVALID_ARG), (_bad(seq_len=0), B.EMS_ERR_INVALID_ARG),
+    (_bad(dtype=7), B.EMS_ERR_INVALID_ARG), (_bad(head_dim=96), B.EMS_ERR_UNSUPPORTED),
+    (_bad(batch=0), B.EMS_ERR_INVALID_ARG), (_bad(softmax_scale=float("nan")), B.EMS_ERR_INVALID_ARG)])
+def test_score_argument_errors(lib, p, code):
+    cp = p.c()
+    dummy = C.c_void_p(256)
+    rc = lib.ems_global_local_score(C.byref(cp), dummy, dummy, dummy, dummy, None, dummy, 1 << 40, None)
+    assert rc == code
+
+
+@pytest.mark.parametrize("p", [_bad(budget=16), _bad(budget=513), _bad(pool_kernel=4),
+                               _bad(pool_kernel=0), _bad(merge_ratio=-0.5),
+                               _bad(merge_ratio=float("nan")), _bad(tau=float("nan"))])
+def test_select_and_merge_argument_errors(lib, p):
+    cp = p.c()
+    dummy = C.c_void_p(256)
+    assert lib.ems_select(C.byref(cp), dummy, dummy, None, dummy, dummy, dummy, 1 << 40, None) \
+        == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_evict_merge(C.byref(cp), *([dummy] * 12), 1 << 40, None) == B.EMS_ERR_INVALID_ARG
+    with pytest.raises(B.EmsError):
+        B.ems_partition_sizes(p)
+
+
+def test_null_pointers_and_workspace_errors(lib):
+    p = _bad()
+    cp = p.c()
+    d = C.c_void_p(256)
+    assert lib.ems_global_local_score(None, d, d, d, d, None, d, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_global_local_score(C.byref(cp), None, d, d, d, None, d, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_global_local_score(C.byref(cp), d, d, d, None, None, d, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_global_local_score(C.byref(cp), d, d, d, d, None, None, 1 << 40, None) == B.EMS_ERR_WORKSPACE
+    assert lib.ems_global_local_score(C.byref(cp), d, d, d, d, None, d, 16, None) == B.EMS_ERR_WORKSPACE
+    assert lib.ems_global_local_score(C.byref(cp), d, d, d, d, None, C.c_void_p(260), 1 << 40, None) == B.EMS_ERR_WORKSPACE
+    assert lib.ems_select(C.byref(cp), d, d, None, None, d, d, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_select(C.byref(cp), d, d, None, d, None, d, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_select(C.byref(cp), d, d, None, d, d, d, 8, None) == B.EMS_ERR_WORKSPACE
+    args = [d] * 12
+    args[3] = None     # tbm_idx missing while N_tbm > 0
+    assert lib.ems_evict_merge(C.byref(cp), *args, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_evict_merge(C.byref(cp), *([d] * 12), 8, None) == B.EMS_ERR_WORKSPACE
+    assert lib.ems_workspace_bytes(None, None, None, None) == B.EMS_ERR_INVALID_ARG
