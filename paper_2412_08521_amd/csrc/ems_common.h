@@ -58,6 +58,14 @@ __device__ __forceinline__ void mma<float>(f32x16_t& acc, const frag_t& a, const
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[3], bf[3], acc, 0, 0, 0);
 }
 
+// First product of a chain: the accumulator starts from zero.
+template <typename T>
+__device__ __forceinline__ void mma_first(f32x16_t& acc, const frag_t& a, const frag_t& b)
+{
+    acc = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    mma<T>(acc, a, b);
+}
+
 // 32x32 accumulator: register r of lane l holds output row acc_row(r, l / 32) (the A
 // operand's row) and output column l % 32 (the B operand's column).
 __device__ __forceinline__ constexpr int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }

@@ -58,14 +58,61 @@ __device__ __forceinline__ void stage_store(char* lds, const StageRegs<T, D>& re
     }
 }
 
+// sum of the 16 accumulator-derived values with four independent partial sums
+__device__ __forceinline__ float sum16(const float (&p)[16])
+{
+    float s0 = p[0], s1 = p[1], s2 = p[2], s3 = p[3];
+#pragma unroll
+    for (int r = 4; r < 16; r += 4) { s0 += p[r]; s1 += p[r + 1]; s2 += p[r + 2]; s3 += p[r + 3]; }
+    return (s0 + s1) + (s2 + s3);
+}
+
+__device__ __forceinline__ f32x16_t zero_acc()
+{
+    return f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+}
+
 // ------------------------------------------------------------------------------------
 // Pass 1.  Block = (b, q-head, tile of 4 * 32 * kSub query rows).  Each wave keeps its
 // queries in registers as the MFMA B operand (queries -> lanes) and streams key tiles
 // through LDS as the A operand (keys -> accumulator registers), so the running row
 // maximum and row sum of the online softmax are per-lane scalars.
 // ------------------------------------------------------------------------------------
+
+// One 32-key x 32-query tile of the online softmax.  kMasked tiles may cross the diagonal.
+template <typename T, int D, bool kMasked>
+__device__ __forceinline__ void pass1_tile(const frag_t (&ak)[Tile<T, D>::kFrags],
+                                           const frag_t (&bq)[Tile<T, D>::kFrags],
+                                           float& m_run, float& l_run, float c,
+                                           int key0, int qi, int half)
+{
+    f32x16_t acc = zero_acc();
+#pragma unroll
+    for (int f = 0; f < Tile<T, D>::kFrags; ++f) mma<T>(acc, ak[f], bq[f]);
+    if (kMasked) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (key0 + acc_row(r, half) > qi) acc[r] = -INFINITY;
+    }
+    float t0 = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+    float t1 = fmaxf(fmaxf(acc[3], acc[4]), acc[5]);
+    float t2 = fmaxf(fmaxf(acc[6], acc[7]), acc[8]);
+    float t3 = fmaxf(fmaxf(acc[9], acc[10]), acc[11]);
+    float t4 = fmaxf(fmaxf(acc[12], acc[13]), acc[14]);
+    t0 = fmaxf(fmaxf(t0, t1), t2);
+    t3 = fmaxf(fmaxf(t3, t4), acc[15]);
+    const float tmax = fmaxf(t0, t3);
+    const float m_new = fmaxf(m_run, tmax * c);
+    const float m_use = (kMasked && m_new == -INFINITY) ? 0.f : m_new;
+    float p[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) p[r] = exp2_fast(__builtin_fmaf(acc[r], c, -m_use));
+    l_run = __builtin_fmaf(l_run, exp2_fast(m_run - m_use), sum16(p));
+    m_run = m_new;
+}
+
 template <typename T, int D>
-__global__ __launch_bounds__(kBlock) void score_pass1_kernel(ScoreArgs a)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_pass1_kernel(ScoreArgs a)
 {
     constexpr int kSub = Sub<T>::kSub;
     constexpr int kStageRows = Sub<T>::kStageRows;
@@ -91,7 +138,8 @@ __global__ __launch_bounds__(kBlock) void score_pass1_kernel(ScoreArgs a)
 
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int col = lane & 31, half = lane >> 5;
-    const int q0 = rt * kRowsPerBlock + wave * 32 * kSub;
+    const int q_block0 = rt * kRowsPerBlock;
+    const int q0 = q_block0 + wave * 32 * kSub;
 
     frag_t bq[kSub][kFrags];
 #pragma unroll
@@ -106,6 +154,18 @@ __global__ __launch_bounds__(kBlock) void score_pass1_kernel(ScoreArgs a)
 #pragma unroll
     for (int s = 0; s < kSub; ++s) { m_run[s] = -INFINITY; l_run[s] = 0.f; }
 
+    // exponents of the tile whose exp2 is still outstanding (they belong to the last query
+    // subtile; -inf contributes nothing)
+    f32x16_t pend;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pend[r] = -INFINITY;
+    auto flush_pend1 = [&]() {
+        float tot = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { tot += exp2_fast(pend[r]); pend[r] = -INFINITY; }
+        l_run[kSub - 1] += tot;
+    };
+
     const int last_key = min(N, (rt + 1) * kRowsPerBlock);      // exclusive
     const int n_tiles = (last_key + kStageRows - 1) / kStageRows;
     const float c = a.scale_log2e;
@@ -118,44 +178,102 @@ __global__ __launch_bounds__(kBlock) void score_pass1_kernel(ScoreArgs a)
     for (int t = 0; t < n_tiles; ++t) {
         if (t + 1 < n_tiles) stage_load<T, D>(pre, K, (t + 1) * kStageRows, N);
         const char* cur = lds[t & 1];
+        const int stage_key0 = t * kStageRows;
+        if (stage_key0 + kStageRows - 1 <= q_block0) {
+            // Steady state: every key of the stage is visible to every query of the block.
+            // Software pipeline written out slot by slot: each MFMA of tile t+1 is followed
+            // by a share of tile t's online-softmax work.  The last tile's running maximum
+            // is settled before the barrier; its exponentials (`pend`) are summed under the
+            // first tile of the next stage.
+            constexpr int kKS = kStageRows / 32, kTiles = kKS * kSub, kEps = 16 / kFrags;
+            frag_t ak[kKS][kFrags];
 #pragma unroll
-        for (int ks = 0; ks < kStageRows / 32; ++ks) {
-            const int key0 = t * kStageRows + ks * 32;
-            // wave-uniform: does any of this wave's queries see any of these keys?
-            if (key0 > q0 + 32 * kSub - 1) continue;
-            frag_t ak[kFrags];
+            for (int ks = 0; ks < kKS; ++ks)
 #pragma unroll
-            for (int f = 0; f < kFrags; ++f)
-                ak[f] = *reinterpret_cast<const frag_t*>(cur + (ks * 32 + col) * kStride + f * 32 + half * 16);
+                for (int f = 0; f < kFrags; ++f)
+                    ak[ks][f] = *reinterpret_cast<const frag_t*>(cur + (ks * 32 + col) * kStride + f * 32 + half * 16);
+            f32x16_t acc[2];
+            float pv[kEps], ls[kEps];
 #pragma unroll
-            for (int s = 0; s < kSub; ++s) {
-                const int qs0 = q0 + s * 32;
-                if (key0 > qs0 + 31) continue;                   // wave-uniform
-                f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int e = 0; e < kEps; ++e) { pv[e] = 0.f; ls[e] = 0.f; }
 #pragma unroll
-                for (int f = 0; f < kFrags; ++f) mma<T>(acc, ak[f], bq[s][f]);
-                const int qi = qs0 + col;
-                if (key0 + 31 > qs0) {                           // tile crosses the diagonal
+            for (int f = 0; f < kFrags; ++f) {
+                if (f == 0) mma_first<T>(acc[0], ak[0][0], bq[0][0]);
+                else mma<T>(acc[0], ak[0][f], bq[0][f]);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (key0 + acc_row(r, half) > qi) acc[r] = -INFINITY;
-                }
-                float tmax = acc[0];
+                for (int e = 0; e < kEps; ++e) ls[e] += pv[e];
 #pragma unroll
-                for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, acc[r]);
-                const float m_new = fmaxf(m_run[s], tmax * c);
-                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-                float sum = 0.f;
+                for (int e = 0; e < kEps; ++e) pv[e] = exp2_fast(pend[f * kEps + e]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            {
+                float tot = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sum += exp2_fast(__builtin_fmaf(acc[r], c, -m_use));
-                l_run[s] = l_run[s] * exp2_fast(m_run[s] - m_use) + sum;
+                for (int e = 0; e < kEps; ++e) tot += ls[e] + pv[e];
+                l_run[kSub - 1] += tot;
+            }
+#pragma unroll
+            for (int t = 0; t < kTiles; ++t) {
+                const int s = t % kSub;
+                const f32x16_t& av = acc[t & 1];
+                // running maximum of the row (finite here: no masked element)
+                float t0 = fmaxf(fmaxf(av[0], av[1]), av[2]);
+                float t1 = fmaxf(fmaxf(av[3], av[4]), av[5]);
+                float t2 = fmaxf(fmaxf(av[6], av[7]), av[8]);
+                float t3 = fmaxf(fmaxf(av[9], av[10]), av[11]);
+                float t4 = fmaxf(fmaxf(av[12], av[13]), av[14]);
+                t0 = fmaxf(fmaxf(t0, t1), t2);
+                t3 = fmaxf(fmaxf(t3, t4), av[15]);
+                const float m_new = fmaxf(m_run[s], fmaxf(t0, t3) * c);
+                l_run[s] *= exp2_fast(m_run[s] - m_new);
                 m_run[s] = m_new;
+                if (t + 1 < kTiles) {
+#pragma unroll
+                    for (int e = 0; e < kEps; ++e) { pv[e] = 0.f; ls[e] = 0.f; }
+#pragma unroll
+                    for (int f = 0; f < kFrags; ++f) {
+                        if (f == 0) mma_first<T>(acc[(t + 1) & 1], ak[(t + 1) / kSub][0], bq[(t + 1) % kSub][0]);
+                        else mma<T>(acc[(t + 1) & 1], ak[(t + 1) / kSub][f], bq[(t + 1) % kSub][f]);
+#pragma unroll
+                        for (int e = 0; e < kEps; ++e) ls[e] += pv[e];
+#pragma unroll
+                        for (int e = 0; e < kEps; ++e)
+                            pv[e] = exp2_fast(__builtin_fmaf(av[f * kEps + e], c, -m_new));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    float tot = 0.f;
+#pragma unroll
+                    for (int e = 0; e < kEps; ++e) tot += ls[e] + pv[e];
+                    l_run[s] += tot;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) pend[r] = __builtin_fmaf(av[r], c, -m_new);
+                }
+            }
+        } else {
+            // stages that touch the diagonal: skip tiles above it, mask tiles across it
+            flush_pend1();
+#pragma unroll
+            for (int ks = 0; ks < kStageRows / 32; ++ks) {
+                const int key0 = stage_key0 + ks * 32;
+                if (key0 > q0 + 32 * kSub - 1) continue;        // wave-uniform
+                frag_t ak[kFrags];
+#pragma unroll
+                for (int f = 0; f < kFrags; ++f)
+                    ak[f] = *reinterpret_cast<const frag_t*>(cur + (ks * 32 + col) * kStride + f * 32 + half * 16);
+#pragma unroll
+                for (int s = 0; s < kSub; ++s) {
+                    const int qs0 = q0 + s * 32;
+                    if (key0 > qs0 + 31) continue;               // wave-uniform
+                    pass1_tile<T, D, true>(ak, bq[s], m_run[s], l_run[s], c, key0, qs0 + col, half);
+                }
             }
         }
         if (t + 1 < n_tiles) stage_store<T, D>(lds[(t + 1) & 1], pre);
         __syncthreads();
     }
 
+    flush_pend1();
     float* lse2 = a.lse2 + (size_t)(b * a.q_heads + h) * N;
     float* lse_nat = a.lse_opt ? a.lse_opt + (size_t)(b * a.q_heads + h) * N : nullptr;
 #pragma unroll
@@ -182,8 +300,40 @@ __global__ __launch_bounds__(kBlock) void score_pass1_kernel(ScoreArgs a)
 // the work per block (causal load balance) and let blocks that run together read the same
 // Q rows; their partial sums are added in a fixed order by score_reduce_kernel.
 // ------------------------------------------------------------------------------------
+
+// One 32-row x 32-key tile: weights 2^(c*S - lse2) added into the lane's column sums.
+// kEdge tiles may cross the diagonal and may hold last-window rows.
+template <typename T, int D, bool kEdge>
+__device__ __forceinline__ void pass2_tile(const frag_t (&aq)[Tile<T, D>::kFrags],
+                                           const frag_t (&bk)[Tile<T, D>::kFrags],
+                                           const float (&lse_r)[16], float c,
+                                           float& glo, float& loc,
+                                           int row0, int kj, int half, int win0)
+{
+    f32x16_t acc = zero_acc();
+#pragma unroll
+    for (int f = 0; f < Tile<T, D>::kFrags; ++f) mma<T>(acc, aq[f], bk[f]);
+    float p[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) p[r] = exp2_fast(__builtin_fmaf(acc[r], c, -lse_r[r]));
+    if (kEdge) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (row0 + acc_row(r, half) < kj) p[r] = 0.f;
+    }
+    glo += sum16(p);
+    if (kEdge) {
+        if (row0 + 31 >= win0) {                                 // wave-uniform
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (row0 + acc_row(r, half) < win0) p[r] = 0.f;
+            loc += sum16(p);
+        }
+    }
+}
+
 template <typename T, int D>
-__global__ __launch_bounds__(kBlock) void score_pass2_kernel(ScoreArgs a)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_pass2_kernel(ScoreArgs a)
 {
     constexpr int kSub = Sub<T>::kSub;
     constexpr int kStageRows = Sub<T>::kStageRows;
@@ -228,6 +378,20 @@ __global__ __launch_bounds__(kBlock) void score_pass2_kernel(ScoreArgs a)
     float glo[kSub], loc[kSub];
 #pragma unroll
     for (int s = 0; s < kSub; ++s) { glo[s] = 0.f; loc[s] = 0.f; }
+    // steady-state partial column sums (independent add chains) and the exponents of the
+    // tile whose exp2 is still outstanding (-inf contributes nothing)
+    float part[kSub][16 / kFrags];
+#pragma unroll
+    for (int s = 0; s < kSub; ++s)
+#pragma unroll
+        for (int e = 0; e < 16 / kFrags; ++e) part[s][e] = 0.f;
+    f32x16_t pend;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pend[r] = -INFINITY;
+    auto flush_pend = [&]() {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { part[kSub - 1][r % (16 / kFrags)] += exp2_fast(pend[r]); pend[r] = -INFINITY; }
+    };
 
     const int tiles_per_head = (r_end - r_begin + kStageRows - 1) / kStageRows;
     const int n_tiles = tiles_per_head * G;
@@ -269,48 +433,92 @@ __global__ __launch_bounds__(kBlock) void score_pass2_kernel(ScoreArgs a)
         const char* cur = lds[t & 1];
         const float* cur_lse = lds_lse[t & 1];
         const int row_tile0 = row0_of(t);
+        // steady state: all rows of the stage are below every key of the block's tile and
+        // above the last window (rows past the end only occur together with window rows)
+        const bool interior = row_tile0 >= key_base + kKeysPerBlock - 1 && row_tile0 + kStageRows <= win0;
+        if (interior) {
+            // Software pipeline over the stage's tiles, written out slot by slot: each MFMA
+            // of tile t+1 is followed by the exp2/add work of a few elements of tile t, so
+            // the matrix pipe and the vector ALU of this wave are busy at the same time.
+            // The last tile's exponents are carried over (`pend`) and finished under the
+            // first tile of the next stage.
+            constexpr int kRS = kStageRows / 32, kTiles = kRS * kSub, kEps = 16 / kFrags;
+            frag_t aq[kRS][kFrags];
+            float lse_r[kRS][16];
 #pragma unroll
-        for (int rs = 0; rs < kStageRows / 32; ++rs) {
-            const int row0 = row_tile0 + rs * 32;
-            if (row0 + 31 < k0 || row0 >= N) continue;           // wave-uniform
-            frag_t aq[kFrags];
+            for (int rs = 0; rs < kRS; ++rs) {
 #pragma unroll
-            for (int f = 0; f < kFrags; ++f)
-                aq[f] = *reinterpret_cast<const frag_t*>(cur + (rs * 32 + col) * kStride + f * 32 + half * 16);
-            float lse_r[16];
+                for (int f = 0; f < kFrags; ++f)
+                    aq[rs][f] = *reinterpret_cast<const frag_t*>(cur + (rs * 32 + col) * kStride + f * 32 + half * 16);
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(cur_lse + rs * 32 + 8 * q4 + 4 * half);
-                lse_r[4 * q4 + 0] = v[0]; lse_r[4 * q4 + 1] = v[1];
-                lse_r[4 * q4 + 2] = v[2]; lse_r[4 * q4 + 3] = v[3];
-            }
-            const bool in_window = row0 + 31 >= win0;            // wave-uniform
-#pragma unroll
-            for (int s = 0; s < kSub; ++s) {
-                const int ks0 = k0 + s * 32;
-                if (row0 + 31 < ks0) continue;                   // wave-uniform
-                f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int f = 0; f < kFrags; ++f) mma<T>(acc, aq[f], bk[s][f]);
-                float p[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) p[r] = exp2_fast(__builtin_fmaf(acc[r], c, -lse_r[r]));
-                if (row0 < ks0 + 31) {                           // tile crosses the diagonal
-                    const int kj = ks0 + col;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (row0 + acc_row(r, half) < kj) p[r] = 0.f;
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(cur_lse + rs * 32 + 8 * q4 + 4 * half);
+                    lse_r[rs][4 * q4 + 0] = v[0]; lse_r[rs][4 * q4 + 1] = v[1];
+                    lse_r[rs][4 * q4 + 2] = v[2]; lse_r[rs][4 * q4 + 3] = v[3];
                 }
-                float sum = 0.f;
+            }
+            f32x16_t acc[2];
+            float pv[kEps];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sum += p[r];
-                glo[s] += sum;
-                if (in_window) {
-                    float lsum = 0.f;
+            for (int e = 0; e < kEps; ++e) pv[e] = 0.f;
+#pragma unroll
+            for (int f = 0; f < kFrags; ++f) {
+                if (f == 0) mma_first<T>(acc[0], aq[0][0], bk[0][0]);
+                else mma<T>(acc[0], aq[0][f], bk[0][f]);
+#pragma unroll
+                for (int e = 0; e < kEps; ++e) part[kSub - 1][e] += pv[e];
+#pragma unroll
+                for (int e = 0; e < kEps; ++e) pv[e] = exp2_fast(pend[f * kEps + e]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) part[kSub - 1][e] += pv[e];
+#pragma unroll
+            for (int t = 0; t < kTiles; ++t) {
+                if (t + 1 < kTiles) {
+#pragma unroll
+                    for (int e = 0; e < kEps; ++e) pv[e] = 0.f;
+#pragma unroll
+                    for (int f = 0; f < kFrags; ++f) {
+                        if (f == 0) mma_first<T>(acc[(t + 1) & 1], aq[(t + 1) / kSub][0], bk[(t + 1) % kSub][0]);
+                        else mma<T>(acc[(t + 1) & 1], aq[(t + 1) / kSub][f], bk[(t + 1) % kSub][f]);
+#pragma unroll
+                        for (int e = 0; e < kEps; ++e) part[t % kSub][e] += pv[e];
+#pragma unroll
+                        for (int e = 0; e < kEps; ++e)
+                            pv[e] = exp2_fast(__builtin_fmaf(acc[t & 1][f * kEps + e], c, -lse_r[t / kSub][f * kEps + e]));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                    for (int e = 0; e < kEps; ++e) part[t % kSub][e] += pv[e];
+                } else {
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        lsum += (row0 + acc_row(r, half) >= win0) ? p[r] : 0.f;
-                    loc[s] += lsum;
+                        pend[r] = __builtin_fmaf(acc[t & 1][r], c, -lse_r[t / kSub][r]);
+                }
+            }
+        } else {
+            flush_pend();
+#pragma unroll
+            for (int rs = 0; rs < kStageRows / 32; ++rs) {
+                const int row0 = row_tile0 + rs * 32;
+                if (row0 + 31 < k0 || row0 >= N) continue;       // wave-uniform
+                frag_t aq[kFrags];
+#pragma unroll
+                for (int f = 0; f < kFrags; ++f)
+                    aq[f] = *reinterpret_cast<const frag_t*>(cur + (rs * 32 + col) * kStride + f * 32 + half * 16);
+                float lse_r[16];
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(cur_lse + rs * 32 + 8 * q4 + 4 * half);
+                    lse_r[4 * q4 + 0] = v[0]; lse_r[4 * q4 + 1] = v[1];
+                    lse_r[4 * q4 + 2] = v[2]; lse_r[4 * q4 + 3] = v[3];
+                }
+#pragma unroll
+                for (int s = 0; s < kSub; ++s) {
+                    const int ks0 = k0 + s * 32;
+                    if (row0 + 31 < ks0) continue;               // wave-uniform
+                    pass2_tile<T, D, true>(aq, bk[s], lse_r, c, glo[s], loc[s], row0, ks0 + col, half, win0);
                 }
             }
         }
@@ -320,6 +528,12 @@ __global__ __launch_bounds__(kBlock) void score_pass2_kernel(ScoreArgs a)
         }
         __syncthreads();
     }
+
+    flush_pend();
+#pragma unroll
+    for (int s = 0; s < kSub; ++s)
+#pragma unroll
+        for (int e = 0; e < 16 / kFrags; ++e) glo[s] += part[s][e];
 
     // the two half-waves hold disjoint row subsets of the same keys
     const int loc_chunk0 = a.loc_chunk0;

@@ -1,0 +1,196 @@
+"""GPU parity at the full sizes of the five benchmark configurations, in the launch
+configuration bench.py times.  Where the fp64 oracle cannot do the whole layer in seconds it
+does whole (batch, kv-head) units of it -- units are independent, which the small tests pin --
+and every unit is additionally checked through properties that hold at any size and through
+the oracle's cheap stages run on the GPU's own upstream output."""
+import numpy as np
+import pytest
+import torch
+
+import ems_inputs
+from oracle import ems_ref
+from paper_2412_08521_amd import binding as B
+from gpu_util import RTOL, RTOL_MERGE, assert_rel, check_band, dev_tensor, ref_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _log(*a):
+    print(*a, flush=True)
+
+
+def _params(w, tau, mode=B.EMS_BF16):
+    return B.EmsParams(w.batch, w.q_heads, w.kv_heads, w.head_dim, w.seq_len, w.window, w.budget,
+                       merge_ratio=w.merge_ratio, tau=tau, pool_kernel=w.pool_kernel, dtype=mode)
+
+
+def _upload(w, mode, layer=0):
+    tdt = torch.float32 if mode == B.EMS_F32 else torch.bfloat16
+    q = torch.empty((w.batch, w.q_heads, w.seq_len, w.head_dim), dtype=tdt, device="cuda")
+    k = torch.empty((w.batch, w.kv_heads, w.seq_len, w.head_dim), dtype=tdt, device="cuda")
+    v = torch.empty_like(k)
+    host = []
+    for b in range(w.batch):
+        inp = ems_inputs.generate(w, layer=layer, batch_slice=slice(b, b + 1))
+        q[b].copy_(dev_tensor(inp.q[0], mode)); k[b].copy_(dev_tensor(inp.k[0], mode))
+        v[b].copy_(dev_tensor(inp.v[0], mode))
+        host.append(inp)
+    return q, k, v, host
+
+
+def _run_chain(p, q, k, v):
+    s_glo, s_loc = B.ems_global_local_score(p, q, k)
+    imp, tbm, pooled = B.ems_select(p, s_glo, s_loc, want_pooled=True)
+    out = B.ems_evict_merge(p, k, v, imp, tbm)
+    torch.cuda.synchronize()
+    return s_glo, s_loc, imp, tbm, pooled, out
+
+
+def _check_unit_against_oracle(p, w, host_b, b, kvh, s_glo, s_loc, rtol):
+    """Whole-unit element-wise score parity: the G q-heads of one (batch, kv-head)."""
+    G = w.q_heads // w.kv_heads
+    qf = host_b.f32("q")[:, kvh * G:(kvh + 1) * G]
+    kf = host_b.f32("k")[:, kvh:kvh + 1]
+    rp = ems_ref.RefParams(1, G, 1, w.head_dim, w.seq_len, w.window, softmax_scale=p.softmax_scale)
+    o_glo, o_loc = ems_ref.score(rp, qf, kf)
+    e1 = assert_rel(s_glo[b, kvh].cpu().numpy(), o_glo[0, 0], rtol, f"s_glo[{b},{kvh}]")
+    e2 = assert_rel(s_loc[b, kvh].cpu().numpy(), o_loc[0, 0], rtol, f"s_loc[{b},{kvh}]")
+    _log(f"  unit ({b},{kvh}): rel err glo {e1:.2e} loc {e2:.2e}")
+    return o_glo[0, 0], o_loc[0, 0]
+
+
+def _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out, mode):
+    """Holds at any size, checked on every (batch, kv-head)."""
+    G = w.q_heads // w.kv_heads
+    n_imp, n_tbm = B.ems_partition_sizes(p)
+    # every causal softmax row sums to one
+    np.testing.assert_allclose(s_glo.double().sum(-1).cpu().numpy(), G * w.seq_len, rtol=2e-4)
+    np.testing.assert_allclose(s_loc.double().sum(-1).cpu().numpy(), G * w.window, rtol=2e-4)
+    assert (s_loc <= s_glo * (1 + 1e-5) + 1e-12).all() and (s_loc >= 0).all()
+    rp = ref_params(p)
+    pooled_n = pooled.cpu().numpy()
+    imp_n, tbm_n = imp.cpu().numpy(), tbm.cpu().numpy()
+    # Eq. 2 + pooling of the GPU's own scores, then the partition of the GPU's own keys
+    o_pooled = ems_ref.combine_pool(rp, s_glo.cpu().numpy(), s_loc.cpu().numpy())
+    assert_rel(pooled_n, o_pooled, 1e-5, "pooled")
+    x_imp, x_tbm = ems_ref.partition(rp, pooled_n.astype(np.float64))
+    np.testing.assert_array_equal(imp_n, x_imp)
+    np.testing.assert_array_equal(tbm_n, x_tbm)
+    # evict-then-merge of every unit against the oracle's stages on the GPU's index sets
+    kf = np.concatenate([h.f32("k") for h in host])
+    vf = np.concatenate([h.f32("v") for h in host])
+    ref = ems_ref.evict_merge(rp, kf, vf, imp_n, tbm_n)
+    dest = out["tbm_dest"].cpu().numpy()
+    np.testing.assert_allclose(out["tbm_sim"].cpu().numpy(), ref["tbm_sim"], rtol=0, atol=5e-6)
+    margin_ok = dest == ref["tbm_dest"]
+    assert margin_ok.mean() > 0.995, margin_ok.mean()
+    k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge(rp, kf, vf, imp_n, tbm_n, dest)
+    np.testing.assert_array_equal(out["kept_pos"].cpu().numpy(), kept_ref)
+    np.testing.assert_array_equal(out["slot_count"].cpu().numpy(), cnt_ref)
+    for name, want in (("k_out", k_ref), ("v_out", v_ref)):
+        got = out[name].float().cpu().numpy()
+        rms = np.sqrt((want ** 2).mean(-1, keepdims=True))
+        err = np.abs(got - want) / np.maximum(np.abs(want), 1e-2 * np.maximum(rms, 1e-30))
+        assert err.max() <= RTOL_MERGE[mode], f"{name}: {err.max():.3e}"
+    assert out["k_out"].shape == (w.batch, w.kv_heads, w.budget + 1, w.head_dim)
+    assert cnt_ref.sum(-1).min() == n_imp + n_tbm == cnt_ref.sum(-1).max()
+    return dest, ref
+
+
+@pytest.mark.parametrize("mode", [B.EMS_BF16, B.EMS_F32])
+def test_config2_llama2_7b_4k_full(mode):
+    """32 heads MHA, D 128, N 4096, W 32, budget 256: the oracle does the whole layer."""
+    w = ems_inputs.WORKLOADS["llama2_7b_4k"]
+    q, k, v, host = _upload(w, mode)
+    for tau in (0.6, 0.2):
+        p = _params(w, tau, mode)
+        s_glo, s_loc, imp, tbm, pooled, out = _run_chain(p, q, k, v)
+        rp = ref_params(p)
+        o_glo, o_loc = ems_ref.score(rp, host[0].f32("q"), host[0].f32("k"))
+        e1 = assert_rel(s_glo.cpu().numpy(), o_glo, RTOL[mode], "s_glo")
+        e2 = assert_rel(s_loc.cpu().numpy(), o_loc, RTOL[mode], "s_loc")
+        _log(f"config 2 mode {mode} tau {tau}: rel err glo {e1:.2e} loc {e2:.2e}")
+        o_pooled, o_imp, o_tbm = ems_ref.select(rp, o_glo, o_loc)
+        for h in range(w.kv_heads):
+            check_band(imp[0, h].cpu().numpy(), tbm[0, h].cpu().numpy(), o_pooled[0, h],
+                       w.seq_len - w.window, RTOL[mode])
+        if mode == B.EMS_F32:
+            same = (imp.cpu().numpy() == o_imp).all(-1).mean()
+            _log(f"  heads whose important set equals the fp64 oracle's exactly: {same:.2f}")
+        dest, ref = _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out, mode)
+        if tau == 0.2:
+            assert (dest < w.budget).any() and (dest == w.budget).any()
+
+
+def test_config3_mistral_7b_16k():
+    """32/8 GQA, N 16384: two whole kv-head groups against the oracle, properties on all."""
+    w = ems_inputs.WORKLOADS["mistral_7b_16k"]
+    q, k, v, host = _upload(w, B.EMS_BF16)
+    p = _params(w, 0.6)
+    s_glo, s_loc, imp, tbm, pooled, out = _run_chain(p, q, k, v)
+    for kvh in (0, 5):
+        _check_unit_against_oracle(p, w, host[0], 0, kvh, s_glo, s_loc, RTOL[B.EMS_BF16])
+    _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out, B.EMS_BF16)
+    # f32 mode on one group (the same keys, four of the q-heads) to the 1e-5 bar
+    G = w.q_heads // w.kv_heads
+    p1 = B.EmsParams(1, G, 1, w.head_dim, w.seq_len, w.window, dtype=B.EMS_F32)
+    g32, l32 = B.ems_global_local_score(p1, q[:, 2 * G:3 * G].float().contiguous(),
+                                        k[:, 2:3].float().contiguous())
+    rp = ems_ref.RefParams(1, G, 1, w.head_dim, w.seq_len, w.window)
+    o_glo, o_loc = ems_ref.score(rp, host[0].f32("q")[:, 2 * G:3 * G], host[0].f32("k")[:, 2:3])
+    e1 = assert_rel(g32.cpu().numpy(), o_glo, RTOL[B.EMS_F32], "f32 s_glo")
+    e2 = assert_rel(l32.cpu().numpy(), o_loc, RTOL[B.EMS_F32], "f32 s_loc")
+    _log(f"config 3 f32 mode group 2: rel err glo {e1:.2e} loc {e2:.2e}")
+
+
+def test_config4_llama3_8b_32k():
+    """Batch 4, 32/8 GQA, N 32768, W 64, budget 128 -- the benchmark workload."""
+    w = ems_inputs.WORKLOADS["llama3_8b_32k"]
+    q, k, v, host = _upload(w, B.EMS_BF16)
+    p = _params(w, 0.6)
+    s_glo, s_loc, imp, tbm, pooled, out = _run_chain(p, q, k, v)
+    for b, kvh in ((0, 0), (3, 6)):
+        o_glo, o_loc = _check_unit_against_oracle(p, w, host[b], b, kvh, s_glo, s_loc, RTOL[B.EMS_BF16])
+        rp1 = ems_ref.RefParams(1, 1, 1, w.head_dim, w.seq_len, w.window, budget=w.budget,
+                                merge_ratio=w.merge_ratio, pool_kernel=w.pool_kernel)
+        o_pooled, _, _ = ems_ref.select(rp1, o_glo[None, None], o_loc[None, None])
+        check_band(imp[b, kvh].cpu().numpy(), tbm[b, kvh].cpu().numpy(), o_pooled[0, 0],
+                   w.seq_len - w.window, RTOL[B.EMS_BF16])
+    _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out, B.EMS_BF16)
+    # a second run gives the same bits (no atomics, fixed reduction order)
+    again = _run_chain(p, q, k, v)
+    assert torch.equal(again[0], s_glo) and torch.equal(again[1], s_loc)
+    assert torch.equal(again[2], imp) and torch.equal(again[5]["k_out"], out["k_out"])
+    # merge-heavy variant of the same workload
+    p2 = _params(w, -2.0)
+    out2 = B.ems_evict_merge(p2, k, v, imp, tbm)
+    _check_properties_all_units(p2, w, host, s_glo, s_loc, imp, tbm, pooled, out2, B.EMS_BF16)
+    assert (out2["slot_count"][..., -1] == 0).all()
+
+
+def test_config5_extreme_128k_two_layers():
+    """32/8 GQA, N 131072, budget 2048: layers 0 and 31 of the 32 sequential layers (each
+    layer has its own seeded inputs and is independent of the others)."""
+    w = ems_inputs.WORKLOADS["extreme_128k"]
+    for layer in (0, 31):
+        _log(f"config 5 layer {layer}")
+        q, k, v, host = _upload(w, B.EMS_BF16, layer=layer)
+        p = _params(w, 0.6)
+        s_glo, s_loc, imp, tbm, pooled, out = _run_chain(p, q, k, v)
+        _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out, B.EMS_BF16)
+        if layer == 0:
+            # one q-head against its kv-head as a problem of its own, full length, vs the oracle
+            p1 = B.EmsParams(1, 1, 1, w.head_dim, w.seq_len, w.window)
+            g1, l1 = B.ems_global_local_score(p1, q[:, 9:10].contiguous(), k[:, 2:3].contiguous())
+            rp = ems_ref.RefParams(1, 1, 1, w.head_dim, w.seq_len, w.window)
+            o_glo, o_loc = ems_ref.score(rp, host[0].f32("q")[:, 9:10], host[0].f32("k")[:, 2:3])
+            e1 = assert_rel(g1.cpu().numpy(), o_glo, RTOL[B.EMS_BF16], "s_glo head 9")
+            e2 = assert_rel(l1.cpu().numpy(), o_loc, RTOL[B.EMS_BF16], "s_loc head 9")
+            _log(f"  q-head 9 alone: rel err glo {e1:.2e} loc {e2:.2e}")
+            p2 = _params(w, 0.15)
+            out2 = B.ems_evict_merge(p2, k, v, imp, tbm)
+            dest, _ = _check_properties_all_units(p2, w, host, s_glo, s_loc, imp, tbm, pooled, out2,
+                                                  B.EMS_BF16)
+            assert (dest < w.budget).any()
+        del q, k, v, host
+        torch.cuda.empty_cache()
