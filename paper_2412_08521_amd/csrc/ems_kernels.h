@@ -21,6 +21,7 @@ struct ScoreArgs {
     int chunk_rows;     // rows per chunk (multiple of 64)
     int loc_chunk0;     // first chunk that holds a last-window row
     float scale_log2e;  // softmax scale * log2(e)
+    int p1_groups, p1_per_group;  // pass-1 work grouping per XCD (set by the launcher)
 };
 
 struct SelectArgs {

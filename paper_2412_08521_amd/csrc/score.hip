@@ -22,8 +22,10 @@ constexpr int kBlock = kWavesPerBlock * kWave;
 template <typename T> struct Sub { static constexpr int kSub = 2; static constexpr int kStageRows = 64; };
 template <> struct Sub<float> { static constexpr int kSub = 1; static constexpr int kStageRows = 32; };
 
-// Stage kStageRows rows (row0 onwards of a [n_rows, D] matrix) into registers; rows past
-// the end read as zeros.
+// Stage kStageRows rows (row0 onwards of a [n_rows, D] matrix, n_rows * row bytes < 4 GiB)
+// into registers.  Rows past the end re-read the last row: callers never let such rows
+// contribute (they are masked by causality or carry an infinite log-sum-exp), so no
+// branch and no zero fill is needed on this path.
 template <typename T, int D> struct StageRegs {
     static constexpr int kPerThread = Tile<T, D>::kChunksPerRow * Sub<T>::kStageRows / kBlock;
     frag_t r[kPerThread];
@@ -39,8 +41,9 @@ __device__ __forceinline__ void stage_load(StageRegs<T, D>& regs, const T* base,
     for (int i = 0; i < kPerThread; ++i) {
         const int c = threadIdx.x + i * kBlock;
         const int row = c / kCpr, col = c % kCpr;
-        const int grow = row0 + row;
-        regs.r[i] = load_frag_or_zero(base, ((size_t)grow * kCpr + col) * 16, grow < n_rows);
+        const unsigned grow = (unsigned)min(row0 + row, n_rows - 1);
+        const unsigned off = grow * (unsigned)Tile<T, D>::kRowBytes + (unsigned)col * 16u;
+        regs.r[i] = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(base) + off);
     }
 }
 
@@ -56,6 +59,22 @@ __device__ __forceinline__ void stage_store(char* lds, const StageRegs<T, D>& re
         const int row = c / kCpr, col = c % kCpr;
         *reinterpret_cast<frag_t*>(lds + row * Tile<T, D>::kLdsStride + col * 16) = regs.r[i];
     }
+}
+
+// The hardware deals workgroups to the 8 XCDs (each with its own L2) round-robin in launch
+// order.  Work is cut into groups of `per_group` consecutive work items that stream the
+// same operand; group g is given to XCD g % 8 so that the group shares one L2.  Returns
+// the linear work-item index, or -1 for a padding block.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int xcd_work_item(int n_groups, int per_group)
+{
+    const int xcd = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
+    const int group = (k / per_group) * kXcds + xcd;
+    return group < n_groups ? group * per_group + k % per_group : -1;
+}
+static unsigned xcd_grid(int n_groups, int per_group)
+{
+    return (unsigned)(kXcds * ((n_groups + kXcds - 1) / kXcds) * per_group);
 }
 
 // sum of the 16 accumulator-derived values with four independent partial sums
@@ -125,11 +144,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int N = a.seq_len;
     const int n_row_tiles = (N + kRowsPerBlock - 1) / kRowsPerBlock;
     const int G = a.q_heads / a.kv_heads;
-    // (b, kv-head) outermost so that blocks in flight share one K; heaviest row tiles first.
-    int bid = blockIdx.x;
+    int bid = xcd_work_item(a.p1_groups, a.p1_per_group);
+    if (bid < 0) return;
     const int g = bid % G; bid /= G;
-    const int rt = n_row_tiles - 1 - (bid % n_row_tiles); bid /= n_row_tiles;
-    const int bkv = bid;                          // b * kv_heads + kv
+    const int BKV = a.batch * a.kv_heads;
+    int rt, bkv;                                  // bkv = b * kv_heads + kv
+    if (a.p1_groups == BKV) { rt = n_row_tiles - 1 - (bid % n_row_tiles); bkv = bid / n_row_tiles; }
+    else { bkv = bid % BKV; rt = n_row_tiles - 1 - (bid / BKV); }   // heaviest row tiles first
     const int b = bkv / a.kv_heads, kvh = bkv % a.kv_heads;
     const int h = kvh * G + g;
 
@@ -349,10 +370,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int n_key_tiles = (N + kKeysPerBlock - 1) / kKeysPerBlock;
     const int n_chunks = a.n_chunks, R = a.chunk_rows;
 
-    int bid = blockIdx.x;
+    int bid = xcd_work_item(a.batch * a.kv_heads * n_chunks, n_key_tiles);
+    if (bid < 0) return;
+    // groups in heaviest-first order (late row chunks see the most key tiles), heads
+    // innermost, so that the groups an XCD receives add up to the same work
     const int J = bid % n_key_tiles; bid /= n_key_tiles;
-    const int I = n_chunks - 1 - (bid % n_chunks); bid /= n_chunks;
-    const int bkv = bid;
+    const int BKV = a.batch * a.kv_heads;
+    const int bkv = bid % BKV;
+    const int I = n_chunks - 1 - bid / BKV;
     const int key_base = J * kKeysPerBlock;
     // rows of this chunk that can see any key of this tile
     const int r_begin = max(I * R, (key_base / kStageRows) * kStageRows);
@@ -412,12 +437,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     auto row0_of = [&](int t) { return r_begin + (t % tiles_per_head) * kStageRows; };
 
     StageRegs<T, D> pre;
-    float pre_lse = INFINITY;
+    float pre_lse = 0.f;
+    int pre_row = 0;
     stage_load<T, D>(pre, q_of(0), row0_of(0), N);
     if (threadIdx.x < kStageRows) {
-        const int r = row0_of(0) + threadIdx.x;
-        pre_lse = r < N ? lse_of(0)[r] * lse_mul : INFINITY;
-        lds_lse[0][threadIdx.x] = pre_lse;
+        pre_row = row0_of(0) + threadIdx.x;
+        pre_lse = lse_of(0)[min(pre_row, N - 1)];
+        lds_lse[0][threadIdx.x] = pre_row < N ? pre_lse * lse_mul : INFINITY;
     }
     stage_store<T, D>(lds[0], pre);
     __syncthreads();
@@ -426,8 +452,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         if (t + 1 < n_tiles) {
             stage_load<T, D>(pre, q_of(t + 1), row0_of(t + 1), N);
             if (threadIdx.x < kStageRows) {
-                const int r = row0_of(t + 1) + threadIdx.x;
-                pre_lse = r < N ? lse_of(t + 1)[r] * lse_mul : INFINITY;
+                pre_row = row0_of(t + 1) + threadIdx.x;
+                pre_lse = lse_of(t + 1)[min(pre_row, N - 1)];    // used only after the tile's work
             }
         }
         const char* cur = lds[t & 1];
@@ -524,7 +550,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         }
         if (t + 1 < n_tiles) {
             stage_store<T, D>(lds[(t + 1) & 1], pre);
-            if (threadIdx.x < kStageRows) lds_lse[(t + 1) & 1][threadIdx.x] = pre_lse;
+            if (threadIdx.x < kStageRows)
+                lds_lse[(t + 1) & 1][threadIdx.x] = pre_row < N ? pre_lse * lse_mul : INFINITY;
         }
         __syncthreads();
     }
@@ -585,8 +612,13 @@ static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
     constexpr int kRows = kWavesPerBlock * 32 * Sub<T>::kSub;
     const int BKV = a.batch * a.kv_heads, G = a.q_heads / a.kv_heads;
     const int n_row_tiles = (a.seq_len + kRows - 1) / kRows;
-    const unsigned grid1 = (unsigned)(BKV * G * n_row_tiles);
-    hipLaunchKernelGGL((score_pass1_kernel<T, D>), dim3(grid1), dim3(kBlock), 0, st, a);
+    // blocks of one (b, kv-head) stream the same K: one group per XCD when there are enough
+    // heads to keep all XCDs busy, else groups of the G q-heads of one row tile
+    ScoreArgs a1 = a;
+    if (BKV >= kXcds) { a1.p1_groups = BKV; a1.p1_per_group = n_row_tiles * G; }
+    else { a1.p1_groups = BKV * n_row_tiles; a1.p1_per_group = G; }
+    const unsigned grid1 = xcd_grid(a1.p1_groups, a1.p1_per_group);
+    hipLaunchKernelGGL((score_pass1_kernel<T, D>), dim3(grid1), dim3(kBlock), 0, st, a1);
     return hipGetLastError();
 }
 
@@ -596,7 +628,7 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
     constexpr int kKeys = kWavesPerBlock * 32 * Sub<T>::kSub;
     const int BKV = a.batch * a.kv_heads;
     const int n_key_tiles = (a.seq_len + kKeys - 1) / kKeys;
-    const unsigned grid2 = (unsigned)(BKV * a.n_chunks * n_key_tiles);
+    const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_key_tiles);
     hipLaunchKernelGGL((score_pass2_kernel<T, D>), dim3(grid2), dim3(kBlock), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
