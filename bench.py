@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--f32", action="store_true", help="validation mode (f32 MFMA)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of Q (known size) so that rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (every step is independent per "
@@ -112,6 +115,12 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b_) / reps
 
+    if args.calibrate_copy:
+        q_copy = torch.empty_like(q)
+        q_copy.copy_(q)                      # reads and writes q.numel() * itemsize bytes
+        torch.cuda.synchronize()
+        log(f"calibration copy: {q.numel() * q.element_size()} bytes read and written")
+        del q_copy
     for i in range(args.warmup):
         step()
         torch.cuda.synchronize()
@@ -131,10 +140,14 @@ def main():
     flops_pass = 2.0 * w.head_dim * pairs * w.q_heads * w.batch
     peak = PEAK_F32_MFMA_TFLOPS if args.f32 else PEAK_BF16_TFLOPS
     achieved = flops_pass / (ms_pass2 * 1e-3) / 1e12
+    # HBM traffic per launch comes from the committed rocprofv3 counter summary (two --pmc
+    # runs, scaled by a plain copy); null when no summary exists for this workload
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_score_pass2_{w.name}.json")
+    tpath = os.path.join(ROOT, "profiles", f"score_pass2_{w.name}.md")
     if os.path.exists(tpath) and not args.f32:
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        import re
+        m = re.search(r"hbm_bytes_per_launch:\s*([0-9.eE+]+)", open(tpath).read())
+        traffic = float(m.group(1)) if m else None
     roofline = {"bound": "mfma", "kernel": "score_pass2_kernel", "achieved": round(achieved, 2),
                 "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": traffic, "flops_per_launch": flops_pass,
