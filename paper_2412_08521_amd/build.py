@@ -20,7 +20,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-FP32 instruction selection is switched off for device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function"] + os.environ.get("EMS_EXTRA_HIPCC_FLAGS", "").split()
+         "-Wall", "-Wno-unused-function",
+         # the LDS-DMA inline assembly names M0 as clobbered, which clang flags as reserved
+         "-Wno-inline-asm"] + os.environ.get("EMS_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def _stale(out: str, deps) -> bool:

@@ -49,7 +49,7 @@ void partition_sizes(const ems_params* p, int* n_imp, int* n_tbm)
 }
 
 struct ScorePlan {
-    int n_chunks, chunk_rows, loc_chunk0;
+    int n_chunks, chunk_rows, loc_chunk0, n_pad;
     size_t off_lse2, off_part_glo, off_part_loc, total;
 };
 
@@ -75,7 +75,8 @@ ScorePlan plan_score(const ems_params* p)
     s.n_chunks = (N + R - 1) / R;
     s.loc_chunk0 = (N - p->window) / R;
     size_t off = 0;
-    s.off_lse2 = off; off += align_up(sizeof(float) * (size_t)p->batch * p->q_heads * N);
+    s.n_pad = (N + 63) / 64 * 64;
+    s.off_lse2 = off; off += align_up(sizeof(float) * (size_t)p->batch * p->q_heads * s.n_pad);
     s.off_part_glo = off;
     s.off_part_loc = off;
     if (s.n_chunks > 1) {
@@ -154,6 +155,7 @@ static void fill_score_args(ems::ScoreArgs& a, const ems_params* p, const ScoreP
     a.part_loc = w ? reinterpret_cast<float*>(w + plan.off_part_loc) : nullptr;
     a.batch = p->batch; a.q_heads = p->q_heads; a.kv_heads = p->kv_heads;
     a.head_dim = p->head_dim; a.seq_len = p->seq_len; a.window = p->window;
+    a.n_pad = plan.n_pad;
     a.n_chunks = plan.n_chunks; a.chunk_rows = plan.chunk_rows; a.loc_chunk0 = plan.loc_chunk0;
     const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale
                                                 : 1.0 / std::sqrt((double)p->head_dim);   // Eq. 1

@@ -12,11 +12,12 @@ struct ScoreArgs {
     float* s_glo;       // [B*Hkv, N]
     float* s_loc;       // [B*Hkv, N]
     float* lse_opt;     // [B*Hq, N] natural log, nullable
-    float* lse2;        // [B*Hq, N] base-2 log-sum-exp of c*S (workspace; pass 1 writes it)
+    float* lse2;        // [B*Hq, n_pad] base-2 log-sum-exp of c*S, +inf past N (workspace)
     const float* lse_in_nat;  // caller's natural-log row log-sum-exp for pass 2, or null
     float* part_glo;    // [B*Hkv, n_chunks, N] (workspace, n_chunks > 1 only)
     float* part_loc;    // [B*Hkv, n_chunks - loc_chunk0, N]
     int batch, q_heads, kv_heads, head_dim, seq_len, window;
+    int n_pad;          // seq_len rounded up to a multiple of 64
     int n_chunks;       // row chunks of pass 2
     int chunk_rows;     // rows per chunk (multiple of 64)
     int loc_chunk0;     // first chunk that holds a last-window row

@@ -22,43 +22,127 @@ constexpr int kBlock = kWavesPerBlock * kWave;
 template <typename T> struct Sub { static constexpr int kSub = 2; static constexpr int kStageRows = 64; };
 template <> struct Sub<float> { static constexpr int kSub = 1; static constexpr int kStageRows = 32; };
 
-// Stage kStageRows rows (row0 onwards of a [n_rows, D] matrix, n_rows * row bytes < 4 GiB)
-// into registers.  Rows past the end re-read the last row: callers never let such rows
-// contribute (they are masked by causality or carry an infinite log-sum-exp), so no
-// branch and no zero fill is needed on this path.
-template <typename T, int D> struct StageRegs {
-    static constexpr int kPerThread = Tile<T, D>::kChunksPerRow * Sub<T>::kStageRows / kBlock;
-    frag_t r[kPerThread];
-};
+// ---- staging of the streamed operand: global memory -> LDS without passing through
+// registers (global_load_lds_dwordx4), three stages deep.
+//
+// One instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS; which 16 bytes of
+// global memory a lane fetches is free, so rows are stored unpadded with their 16-byte
+// chunks XOR-swizzled by the row number: the 16 lanes that read one chunk column of 16
+// consecutive rows then hit 16 different bank groups.  Rows past the end of the matrix
+// re-read the last row: callers never let such rows contribute (they are masked by
+// causality or carry an infinite log-sum-exp).
+constexpr int kBuf = 3;   // LDS stages: one being read, two in flight
 
 template <typename T, int D>
-__device__ __forceinline__ void stage_load(StageRegs<T, D>& regs, const T* base, int row0, int n_rows)
+__device__ __forceinline__ int swz_key(int row)
 {
-    constexpr int kStageRows = Sub<T>::kStageRows;
-    constexpr int kCpr = Tile<T, D>::kChunksPerRow;
-    constexpr int kPerThread = kCpr * kStageRows / kBlock;
+    return Tile<T, D>::kChunksPerRow >= 16 ? (row & 15) : ((row >> 1) & 7);
+}
+
+template <typename T, int D> struct Stage {
+    static constexpr int kRows = Sub<T>::kStageRows;
+    static constexpr int kRowBytes = Tile<T, D>::kRowBytes;
+    static constexpr int kBytes = kRows * kRowBytes;
+    static constexpr int kCpr = Tile<T, D>::kChunksPerRow;
+    static constexpr int kInstrPerWave = kBytes / 1024 / kWavesPerBlock;   // DMA instructions per wave
+    static_assert(kBytes % (1024 * kWavesPerBlock) == 0, "stage must split evenly over the waves");
+};
+
+// One DMA instruction: every lane moves `kBytes` (16 or 4) from base + off (off per lane,
+// base wave-uniform) to LDS byte address lds_addr + lane * kBytes (lds_addr wave-uniform;
+// the hardware takes it from M0).  Written as inline assembly on purpose: the compiler would
+// otherwise make every later LDS read wait for all DMA in flight, which defeats prefetching
+// more than one stage ahead.  Completion is tracked by hand with wait_vmem().
+template <int kBytes>
+__device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsigned lds_addr)
+{
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_addr);
+    if (kBytes == 16)
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(m0v) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(m0v) : "memory", "m0");
+}
+
+// LDS byte address of a __shared__ object.
+__device__ __forceinline__ unsigned lds_address(const void* p)
+{
+    return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+// This lane's byte offsets inside a stage for the wave's DMA instructions: they depend on
+// the lane and the wave only, so they are computed once per kernel.
+template <typename T, int D> struct StageLane {
+    unsigned off[Stage<T, D>::kInstrPerWave];     // row * row bytes + swizzled chunk * 16
+    int row[Stage<T, D>::kInstrPerWave];
+    __device__ __forceinline__ void init()
+    {
+        using S = Stage<T, D>;
+        const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-        const int c = threadIdx.x + i * kBlock;
-        const int row = c / kCpr, col = c % kCpr;
-        const unsigned grow = (unsigned)min(row0 + row, n_rows - 1);
-        const unsigned off = grow * (unsigned)Tile<T, D>::kRowBytes + (unsigned)col * 16u;
-        regs.r[i] = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(base) + off);
+        for (int j = 0; j < S::kInstrPerWave; ++j) {
+            const int slot = (wave * S::kInstrPerWave + j) * kWave + lane;   // 16-byte slot of the stage
+            row[j] = slot / S::kCpr;
+            const int chunk = (slot % S::kCpr) ^ swz_key<T, D>(row[j]);
+            off[j] = (unsigned)row[j] * (unsigned)S::kRowBytes + (unsigned)chunk * 16u;
+        }
+    }
+};
+
+// Enqueue this wave's share of one stage (rows row0.. of a [n_rows, D] matrix whose byte
+// size is below 4 GiB) into the stage buffer at LDS address `buf_addr`.
+template <typename T, int D>
+__device__ __forceinline__ void stage_issue(const StageLane<T, D>& sl, unsigned buf_addr, const T* base,
+                                            int row0, int n_rows)
+{
+    using S = Stage<T, D>;
+    const int wave = threadIdx.x / kWave;
+    if (row0 + S::kRows <= n_rows) {
+        // whole stage inside the matrix: uniform base, per-lane offsets as they are
+        const char* stage_base = reinterpret_cast<const char*>(base) + (size_t)row0 * S::kRowBytes;
+#pragma unroll
+        for (int j = 0; j < S::kInstrPerWave; ++j)
+            dma_to_lds<16>(stage_base, sl.off[j], buf_addr + (wave * S::kInstrPerWave + j) * 1024);
+    } else {
+#pragma unroll
+        for (int j = 0; j < S::kInstrPerWave; ++j) {
+            const int over = max(row0 + sl.row[j] - (n_rows - 1), 0);      // rows past the end
+            const unsigned off = (unsigned)row0 * (unsigned)S::kRowBytes + sl.off[j] - (unsigned)over * (unsigned)S::kRowBytes;
+            dma_to_lds<16>(base, off, buf_addr + (wave * S::kInstrPerWave + j) * 1024);
+        }
     }
 }
 
+// Operand fragment `chunk` (16 bytes) of row `row` of a staged tile.
 template <typename T, int D>
-__device__ __forceinline__ void stage_store(char* lds, const StageRegs<T, D>& regs)
+__device__ __forceinline__ frag_t stage_frag(const char* buf, int row, int chunk)
 {
-    constexpr int kStageRows = Sub<T>::kStageRows;
-    constexpr int kCpr = Tile<T, D>::kChunksPerRow;
-    constexpr int kPerThread = kCpr * kStageRows / kBlock;
-#pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-        const int c = threadIdx.x + i * kBlock;
-        const int row = c / kCpr, col = c % kCpr;
-        *reinterpret_cast<frag_t*>(lds + row * Tile<T, D>::kLdsStride + col * 16) = regs.r[i];
-    }
+    return *reinterpret_cast<const frag_t*>(buf + row * Stage<T, D>::kRowBytes + ((chunk ^ swz_key<T, D>(row)) << 4));
+}
+
+// Wait until at most kOutstanding of this wave's vector-memory operations are in flight
+// (they complete in order), leaving the other counters alone.
+template <int kOutstanding>
+__device__ __forceinline__ void wait_vmem()
+{
+    static_assert(kOutstanding >= 0 && kOutstanding < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kOutstanding) : "memory");
+}
+
+// The same wait for "nothing in flight", in the form the compiler can see: used once after
+// the stationary operand's ordinary loads, so that the compiler does not re-insert a full
+// wait for them in front of their first use inside the main loop.
+__device__ __forceinline__ void wait_vmem_all_visible()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt left alone
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): a fence would drain the
+// stages still in flight.  Ordering of the LDS traffic is kept by the explicit waits.
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 // The hardware deals workgroups to the 8 XCDs (each with its own L2) round-robin in launch
@@ -136,10 +220,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     constexpr int kSub = Sub<T>::kSub;
     constexpr int kStageRows = Sub<T>::kStageRows;
     constexpr int kFrags = Tile<T, D>::kFrags;
-    constexpr int kStride = Tile<T, D>::kLdsStride;
     constexpr int kRowsPerBlock = kWavesPerBlock * 32 * kSub;
+    constexpr int kLoads = Stage<T, D>::kInstrPerWave;       // DMA operations per wave and stage
 
-    __shared__ __attribute__((aligned(16))) char lds[2][kStageRows * kStride];
+    __shared__ __attribute__((aligned(1024))) char lds[kBuf][Stage<T, D>::kBytes];
 
     const int N = a.seq_len;
     const int n_row_tiles = (N + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -191,14 +275,20 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int n_tiles = (last_key + kStageRows - 1) / kStageRows;
     const float c = a.scale_log2e;
 
-    StageRegs<T, D> pre;
-    stage_load<T, D>(pre, K, 0, N);
-    stage_store<T, D>(lds[0], pre);
-    __syncthreads();
+    wait_vmem_all_visible();
+    const unsigned lds0 = lds_address(&lds[0][0]);
+    StageLane<T, D> sl;
+    sl.init();
+    stage_issue<T, D>(sl, lds0, K, 0, N);
+    if (n_tiles > 1) { stage_issue<T, D>(sl, lds0 + Stage<T, D>::kBytes, K, kStageRows, N); wait_vmem<kLoads>(); }
+    else wait_vmem<0>();
+    block_barrier();
 
     for (int t = 0; t < n_tiles; ++t) {
-        if (t + 1 < n_tiles) stage_load<T, D>(pre, K, (t + 1) * kStageRows, N);
-        const char* cur = lds[t & 1];
+        // the buffer of stage t+2 was last read in iteration t-1, which every wave has left
+        if (t + 2 < n_tiles)
+            stage_issue<T, D>(sl, lds0 + ((t + 2) % kBuf) * Stage<T, D>::kBytes, K, (t + 2) * kStageRows, N);
+        const char* cur = lds[t % kBuf];
         const int stage_key0 = t * kStageRows;
         if (stage_key0 + kStageRows - 1 <= q_block0) {
             // Steady state: every key of the stage is visible to every query of the block.
@@ -212,7 +302,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             for (int ks = 0; ks < kKS; ++ks)
 #pragma unroll
                 for (int f = 0; f < kFrags; ++f)
-                    ak[ks][f] = *reinterpret_cast<const frag_t*>(cur + (ks * 32 + col) * kStride + f * 32 + half * 16);
+                    ak[ks][f] = stage_frag<T, D>(cur, ks * 32 + col, f * 2 + half);
             f32x16_t acc[2];
             float pv[kEps], ls[kEps];
 #pragma unroll
@@ -281,7 +371,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 frag_t ak[kFrags];
 #pragma unroll
                 for (int f = 0; f < kFrags; ++f)
-                    ak[f] = *reinterpret_cast<const frag_t*>(cur + (ks * 32 + col) * kStride + f * 32 + half * 16);
+                    ak[f] = stage_frag<T, D>(cur, ks * 32 + col, f * 2 + half);
 #pragma unroll
                 for (int s = 0; s < kSub; ++s) {
                     const int qs0 = q0 + s * 32;
@@ -290,12 +380,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 }
             }
         }
-        if (t + 1 < n_tiles) stage_store<T, D>(lds[(t + 1) & 1], pre);
-        __syncthreads();
+        // stage t+1 must have landed before anyone reads it; stage t+2 may stay in flight
+        if (t + 2 < n_tiles) wait_vmem<kLoads>(); else wait_vmem<0>();
+        block_barrier();
     }
 
     flush_pend1();
-    float* lse2 = a.lse2 + (size_t)(b * a.q_heads + h) * N;
+    float* lse2 = a.lse2 + (size_t)(b * a.q_heads + h) * a.n_pad;
     float* lse_nat = a.lse_opt ? a.lse_opt + (size_t)(b * a.q_heads + h) * N : nullptr;
 #pragma unroll
     for (int s = 0; s < kSub; ++s) {
@@ -306,10 +397,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         const float L = l_run[s] * exp2_fast(m_run[s] - Mu) + l_o * exp2_fast(m_o - Mu);
         const float v = Mu + log2_fast(L);
         const int qi = q0 + s * 32 + col;
-        if (half == 0 && qi < N) {
-            lse2[qi] = v;
-            if (lse_nat) lse_nat[qi] = v * 0.693147180559945309f;
-        }
+        // rows past the end get +inf: the second pass then gives them weight zero
+        if (half == 0 && qi < a.n_pad) lse2[qi] = qi < N ? v : INFINITY;
+        if (half == 0 && qi < N && lse_nat) lse_nat[qi] = v * 0.693147180559945309f;
     }
 }
 
@@ -359,11 +449,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     constexpr int kSub = Sub<T>::kSub;
     constexpr int kStageRows = Sub<T>::kStageRows;
     constexpr int kFrags = Tile<T, D>::kFrags;
-    constexpr int kStride = Tile<T, D>::kLdsStride;
     constexpr int kKeysPerBlock = kWavesPerBlock * 32 * kSub;
+    constexpr int kLoads = Stage<T, D>::kInstrPerWave + 1;   // DMA operations per wave and stage
 
-    __shared__ __attribute__((aligned(16))) char lds[2][kStageRows * kStride];
-    __shared__ __attribute__((aligned(16))) float lds_lse[2][kStageRows];
+    __shared__ __attribute__((aligned(1024))) char lds[kBuf][Stage<T, D>::kBytes];
+    // every wave stages its own copy of the rows' log-sum-exp
+    __shared__ __attribute__((aligned(256))) float lds_lse[kBuf][kWavesPerBlock][kStageRows];
 
     const int N = a.seq_len, W = a.window;
     const int G = a.q_heads / a.kv_heads;
@@ -427,37 +518,33 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         const int g = t / tiles_per_head;
         return reinterpret_cast<const T*>(a.q) + ((size_t)(b * a.q_heads + kvh * G + g) * N) * D;
     };
-    // row log-sum-exp: base-2 from pass 1's workspace, or the caller's natural-log one
-    const float* lse_src = a.lse_in_nat ? a.lse_in_nat : a.lse2;
-    const float lse_mul = a.lse_in_nat ? 1.44269504088896340736f : 1.0f;
     auto lse_of = [&](int t) {
         const int g = t / tiles_per_head;
-        return lse_src + (size_t)(b * a.q_heads + kvh * G + g) * N;
+        return a.lse2 + (size_t)(b * a.q_heads + kvh * G + g) * a.n_pad;   // padded with +inf
     };
     auto row0_of = [&](int t) { return r_begin + (t % tiles_per_head) * kStageRows; };
+    const unsigned lds0 = lds_address(&lds[0][0]);
+    const unsigned lse0 = lds_address(&lds_lse[0][0][0]) + wave * kStageRows * 4;
+    StageLane<T, D> sl;
+    sl.init();
+    auto issue = [&](int t) {
+        stage_issue<T, D>(sl, lds0 + (t % kBuf) * Stage<T, D>::kBytes, q_of(t), row0_of(t), N);
+        if (kStageRows == kWave || lane < kStageRows)
+            dma_to_lds<4>(lse_of(t), (unsigned)(row0_of(t) + lane) * 4u,
+                          lse0 + (t % kBuf) * (kWavesPerBlock * kStageRows * 4));
+    };
 
-    StageRegs<T, D> pre;
-    float pre_lse = 0.f;
-    int pre_row = 0;
-    stage_load<T, D>(pre, q_of(0), row0_of(0), N);
-    if (threadIdx.x < kStageRows) {
-        pre_row = row0_of(0) + threadIdx.x;
-        pre_lse = lse_of(0)[min(pre_row, N - 1)];
-        lds_lse[0][threadIdx.x] = pre_row < N ? pre_lse * lse_mul : INFINITY;
-    }
-    stage_store<T, D>(lds[0], pre);
-    __syncthreads();
+    wait_vmem_all_visible();
+    issue(0);
+    if (n_tiles > 1) { issue(1); wait_vmem<kLoads>(); }
+    else wait_vmem<0>();
+    block_barrier();
 
     for (int t = 0; t < n_tiles; ++t) {
-        if (t + 1 < n_tiles) {
-            stage_load<T, D>(pre, q_of(t + 1), row0_of(t + 1), N);
-            if (threadIdx.x < kStageRows) {
-                pre_row = row0_of(t + 1) + threadIdx.x;
-                pre_lse = lse_of(t + 1)[min(pre_row, N - 1)];    // used only after the tile's work
-            }
-        }
-        const char* cur = lds[t & 1];
-        const float* cur_lse = lds_lse[t & 1];
+        // the buffer of stage t+2 was last read in iteration t-1, which every wave has left
+        if (t + 2 < n_tiles) issue(t + 2);
+        const char* cur = lds[t % kBuf];
+        const float* cur_lse = lds_lse[t % kBuf][wave];
         const int row_tile0 = row0_of(t);
         // steady state: all rows of the stage are below every key of the block's tile and
         // above the last window (rows past the end only occur together with window rows)
@@ -475,7 +562,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             for (int rs = 0; rs < kRS; ++rs) {
 #pragma unroll
                 for (int f = 0; f < kFrags; ++f)
-                    aq[rs][f] = *reinterpret_cast<const frag_t*>(cur + (rs * 32 + col) * kStride + f * 32 + half * 16);
+                    aq[rs][f] = stage_frag<T, D>(cur, rs * 32 + col, f * 2 + half);
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const f32x4_t v = *reinterpret_cast<const f32x4_t*>(cur_lse + rs * 32 + 8 * q4 + 4 * half);
@@ -532,7 +619,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 frag_t aq[kFrags];
 #pragma unroll
                 for (int f = 0; f < kFrags; ++f)
-                    aq[f] = *reinterpret_cast<const frag_t*>(cur + (rs * 32 + col) * kStride + f * 32 + half * 16);
+                    aq[f] = stage_frag<T, D>(cur, rs * 32 + col, f * 2 + half);
                 float lse_r[16];
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
@@ -548,12 +635,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 }
             }
         }
-        if (t + 1 < n_tiles) {
-            stage_store<T, D>(lds[(t + 1) & 1], pre);
-            if (threadIdx.x < kStageRows)
-                lds_lse[(t + 1) & 1][threadIdx.x] = pre_row < N ? pre_lse * lse_mul : INFINITY;
-        }
-        __syncthreads();
+        // stage t+1 must have landed before anyone reads it; stage t+2 may stay in flight
+        if (t + 2 < n_tiles) wait_vmem<kLoads>(); else wait_vmem<0>();
+        block_barrier();
     }
 
     flush_pend();
@@ -602,6 +686,17 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(ScoreArgs a, int keys
     a.s_loc[(size_t)bkv * N + j] = l;
 }
 
+// A caller's natural-log row log-sum-exp [B*Hq, N] -> the base-2, +inf-padded layout
+// [B*Hq, n_pad] the second pass streams.
+__global__ __launch_bounds__(256) void lse_to_base2_kernel(ScoreArgs a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int bh = blockIdx.y;
+    if (i >= a.n_pad) return;
+    a.lse2[(size_t)bh * a.n_pad + i] =
+        i < a.seq_len ? a.lse_in_nat[(size_t)bh * a.seq_len + i] * 1.44269504088896340736f : INFINITY;
+}
+
 template <typename T> static int keys_per_block() { return kWavesPerBlock * 32 * Sub<T>::kSub; }
 
 int score_keys_per_block(int dtype_is_f32) { return dtype_is_f32 ? keys_per_block<float>() : keys_per_block<bf16_t>(); }
@@ -628,6 +723,11 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
     constexpr int kKeys = kWavesPerBlock * 32 * Sub<T>::kSub;
     const int BKV = a.batch * a.kv_heads;
     const int n_key_tiles = (a.seq_len + kKeys - 1) / kKeys;
+    if (a.lse_in_nat) {
+        dim3 g((a.n_pad + 255) / 256, a.batch * a.q_heads);
+        hipLaunchKernelGGL(lse_to_base2_kernel, g, dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    }
     const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_key_tiles);
     hipLaunchKernelGGL((score_pass2_kernel<T, D>), dim3(grid2), dim3(kBlock), 0, st, a);
     hipError_t e = hipGetLastError();
