@@ -398,3 +398,57 @@ int ems_ref_evict_merge(const ems_ref_params* p, const float* k, const float* v,
     if (rc != REF_OK) return rc;
     return ems_ref_merge(p, k, v, imp_idx, tbm_idx, tbm_dest, k_out, v_out, kept_pos, slot_count);
 }
+
+/* ------------------------------------------------------------------------------------
+ * App. A, "Shared Entry Expansion": tokens that were merged share one cache entry; at
+ * compute time the entry is expanded back to one key/value per token with the help of
+ * the look-up-table (which entry each token went to) and the stored key norms (Sec. 4.2:
+ * only normalised keys are merged, the norm is kept as one scalar per token).
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_expand(const ems_ref_params* p, const double* k_cache, const double* v_cache,
+                   const int32_t* kept_pos, const int32_t* tbm_idx, const int32_t* tbm_dest,
+                   const double* k_norm, double* k_exp, double* v_exp, int32_t* pos_exp)
+{
+    int32_t n_imp, n_tbm;
+    if (ems_ref_sizes(p, &n_imp, &n_tbm) != REF_OK) return REF_BAD;
+    if (!k_cache || !v_cache || !kept_pos || !k_norm || !k_exp || !v_exp || !pos_exp) return REF_BAD;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest)) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, D = p->head_dim;
+    const long Nb = p->budget, W = p->window, E = n_imp + n_tbm + W;
+    for (long u = 0; u < BH; ++u) {
+        const double* Kc = k_cache + u * (Nb + 1) * D;
+        const double* Vc = v_cache + u * (Nb + 1) * D;
+        const double* nrm = k_norm + u * (n_imp + n_tbm);
+        double* Ke = k_exp + u * E * D;
+        double* Ve = v_exp + u * E * D;
+        int32_t* pe = pos_exp + u * E;
+        for (long s = 0; s < n_imp; ++s) {                  /* a centre is its entry */
+            for (long d = 0; d < D; ++d) { Ke[s * D + d] = Kc[s * D + d]; Ve[s * D + d] = Vc[s * D + d]; }
+            pe[s] = kept_pos[u * Nb + s];
+        }
+        for (long i = 0; i < n_tbm; ++i) {
+            const long row = n_imp + i;
+            const int32_t s = tbm_dest[u * n_tbm + i];
+            if (s >= 0 && s < n_imp) {
+                const double nc = nrm[s], ni = nrm[n_imp + i];
+                for (long d = 0; d < D; ++d) {
+                    const double dir = nc > 0.0 ? Kc[s * D + d] / nc : 0.0;   /* entry direction */
+                    Ke[row * D + d] = ni * dir;
+                    Ve[row * D + d] = Vc[s * D + d];
+                }
+                pe[row] = tbm_idx[u * n_tbm + i];
+            } else if (s == Nb) {                           /* zero class: evicted */
+                for (long d = 0; d < D; ++d) { Ke[row * D + d] = 0.0; Ve[row * D + d] = 0.0; }
+                pe[row] = -1;
+            } else {
+                return REF_BAD;
+            }
+        }
+        for (long t = 0; t < W; ++t) {                      /* local tokens are their own entries */
+            const long row = n_imp + n_tbm + t, src = n_imp + t;
+            for (long d = 0; d < D; ++d) { Ke[row * D + d] = Kc[src * D + d]; Ve[row * D + d] = Vc[src * D + d]; }
+            pe[row] = kept_pos[u * Nb + src];
+        }
+    }
+    return REF_OK;
+}

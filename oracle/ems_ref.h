@@ -84,6 +84,19 @@ int ems_ref_evict_merge(const ems_ref_params* p, const float* k, const float* v,
                         int32_t* tbm_dest, double* tbm_sim, double* k_norm_opt,
                         int32_t* slot_count);
 
+/* Shared-entry expansion (App. A, "Shared Entry Expansion"; the position look-up-table of
+ * Sec. 4.2): every kept token gets its run-time key and value back from its entry.
+ * Row order per head: the N_imp centres, the N_tbm to-be-merged tokens (in tbm_idx order),
+ * the L_win local tokens.  A token in entry s with key norm n gets key n * u_s, where
+ * u_s = k_cache[s] / n_centre(s) is the entry's direction, and value v_cache[s]; tokens sent
+ * to the zero class are evicted: zero row, position -1.
+ *   k_cache, v_cache [B,Hkv,budget+1,D] fp64 ; kept_pos [B,Hkv,budget] ; tbm_idx, tbm_dest
+ *   [B,Hkv,N_tbm] ; k_norm [B,Hkv,N_imp+N_tbm] (centres, then TBM tokens)
+ *   k_exp, v_exp [B,Hkv,N_imp+N_tbm+L_win,D] fp64 ; pos_exp [B,Hkv,N_imp+N_tbm+L_win] */
+int ems_ref_expand(const ems_ref_params* p, const double* k_cache, const double* v_cache,
+                   const int32_t* kept_pos, const int32_t* tbm_idx, const int32_t* tbm_dest,
+                   const double* k_norm, double* k_exp, double* v_exp, int32_t* pos_exp);
+
 /* Number of OpenMP threads the score loop will use. */
 int ems_ref_threads(void);
 

@@ -215,3 +215,23 @@ def evict_merge(p: RefParams, k, v, imp_idx, tbm_idx):
                                      _ptr(cnt, C.c_int32)), "evict_merge")
     return dict(k_out=k_out, v_out=v_out, kept_pos=kept, tbm_dest=d, tbm_sim=sim,
                 k_norm=norm, slot_count=cnt)
+
+
+def expand(p: RefParams, k_cache, v_cache, kept_pos, tbm_idx, tbm_dest, k_norm):
+    k_cache, v_cache, k_norm = _f64(k_cache), _f64(v_cache), _f64(k_norm)
+    kept_pos, tbm_idx, tbm_dest = _i32(kept_pos), _i32(tbm_idx), _i32(tbm_dest)
+    n_imp, n_tbm = sizes(p)
+    B, H, D, E = p.batch, p.kv_heads, p.head_dim, n_imp + n_tbm + p.window
+    assert k_cache.shape == (B, H, p.budget + 1, D) and v_cache.shape == k_cache.shape
+    assert kept_pos.shape == (B, H, p.budget) and k_norm.shape == (B, H, n_imp + n_tbm)
+    assert tbm_idx.shape == (B, H, n_tbm) and tbm_dest.shape == (B, H, n_tbm)
+    k_exp = np.empty((B, H, E, D), np.float64)
+    v_exp = np.empty_like(k_exp)
+    pos = np.empty((B, H, E), np.int32)
+    cp = p.c()
+    _check(lib().ems_ref_expand(C.byref(cp), _ptr(k_cache, C.c_double), _ptr(v_cache, C.c_double),
+                                _ptr(kept_pos, C.c_int32), _ptr(tbm_idx, C.c_int32),
+                                _ptr(tbm_dest, C.c_int32), _ptr(k_norm, C.c_double),
+                                _ptr(k_exp, C.c_double), _ptr(v_exp, C.c_double),
+                                _ptr(pos, C.c_int32)), "expand")
+    return k_exp, v_exp, pos
