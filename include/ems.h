@@ -165,6 +165,30 @@ int ems_evict_merge(const ems_params* p, const void* k, const void* v,
                     int32_t* slot_count,
                     void* ws, size_t ws_bytes, void* hip_stream);
 
+/*
+ * Shared-entry expansion (App. A, "Shared Entry Expansion"; the position look-up-table of
+ * Sec. 4.2).  Tokens that were merged share one cache entry; for the attention of the
+ * current layer the compact cache is expanded back to one key / value per kept token.  The
+ * look-up-table is what ems_evict_merge returned: tbm_dest (which entry each to-be-merged
+ * token went to), kept_pos and k_norm (one key norm per token).  Rows per head, in order:
+ * the N_imp centres, the N_tbm to-be-merged tokens (tbm_idx order), the `window` local
+ * tokens -- N_exp = N_imp + N_tbm + window rows.  A token with key norm n in entry s gets
+ * key (n / n_centre(s)) * k_cache[s] (the entry's direction times its own norm) and value
+ * v_cache[s]; centres and local tokens are their own entries; tokens that went to the zero
+ * class are evicted: zero rows with position -1, to be masked by the consumer.
+ *   k_cache, v_cache in : device [B, Hkv, budget + 1, D] `dtype` (k_out / v_out of ems_evict_merge)
+ *   kept_pos         in : device [B, Hkv, budget] i32
+ *   tbm_idx, tbm_dest in: device [B, Hkv, N_tbm] i32 (NULL iff N_tbm == 0)
+ *   k_norm           in : device [B, Hkv, N_imp + N_tbm] f32
+ *   k_exp, v_exp     out: device [B, Hkv, N_exp, D] `dtype`
+ *   pos_exp          out: device [B, Hkv, N_exp] i32 source position, -1 = evicted
+ * No workspace.  Destinations outside [0, N_imp) are treated as the zero class.
+ */
+int ems_expand(const ems_params* p, const void* k_cache, const void* v_cache,
+               const int32_t* kept_pos, const int32_t* tbm_idx, const int32_t* tbm_dest,
+               const float* k_norm, void* k_exp, void* v_exp, int32_t* pos_exp,
+               void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

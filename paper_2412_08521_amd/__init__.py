@@ -4,6 +4,6 @@ The product is the C-ABI library built from csrc/ (see include/ems.h); `binding`
 ctypes front end.  Build with `python -m paper_2412_08521_amd.build`.
 """
 from .binding import (EMS_BF16, EMS_F32, EmsError, EmsParams, ems_attention_lse,  # noqa: F401
-                      ems_evict_merge, ems_global_local_score,
+                      ems_evict_merge, ems_expand, ems_global_local_score,
                       ems_global_local_score_from_lse, ems_partition_sizes, ems_select,
                       ems_version, ems_workspace_bytes)

@@ -25,7 +25,7 @@ EMS_F32 = 1
 
 EXPORTS = ("ems_version", "ems_strerror", "ems_partition_sizes", "ems_workspace_bytes",
            "ems_global_local_score", "ems_attention_lse", "ems_global_local_score_from_lse",
-           "ems_select", "ems_evict_merge")
+           "ems_select", "ems_evict_merge", "ems_expand")
 
 
 class ems_params(C.Structure):
@@ -87,6 +87,7 @@ def lib():
         l.ems_global_local_score_from_lse.argtypes = [P] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         l.ems_select.argtypes = [P] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         l.ems_evict_merge.argtypes = [P] + [C.c_void_p] * 12 + [C.c_size_t, C.c_void_p]
+        l.ems_expand.argtypes = [P] + [C.c_void_p] * 10
         for name in EXPORTS[2:]:
             getattr(l, name).restype = C.c_int
         _lib = l
@@ -258,3 +259,32 @@ def ems_evict_merge(p: EmsParams, k, v, imp_idx, tbm_idx, ws=None, out=None):
     if rc != EMS_OK:
         raise EmsError(rc, "ems_evict_merge")
     return o
+
+
+def ems_expand(p: EmsParams, merged: dict, tbm_idx, out=None):
+    """Expand the compact cache `merged` (the dict ems_evict_merge returned) back to one
+    key / value per kept token -> (k_exp, v_exp, pos_exp)."""
+    n_imp, n_tbm = ems_partition_sizes(p)
+    n_exp = n_imp + n_tbm + p.window
+    dev = merged["k_out"].device
+    _check_tensor(merged["k_out"], (p.batch, p.kv_heads, p.budget + 1, p.head_dim), p.torch_dtype, "k_cache")
+    _check_tensor(merged["v_out"], (p.batch, p.kv_heads, p.budget + 1, p.head_dim), p.torch_dtype, "v_cache")
+    _check_tensor(merged["kept_pos"], (p.batch, p.kv_heads, p.budget), torch.int32, "kept_pos")
+    _check_tensor(merged["k_norm"], (p.batch, p.kv_heads, n_imp + n_tbm), torch.float32, "k_norm")
+    _check_tensor(merged["tbm_dest"], (p.batch, p.kv_heads, n_tbm), torch.int32, "tbm_dest")
+    _check_tensor(tbm_idx, (p.batch, p.kv_heads, n_tbm), torch.int32, "tbm_idx")
+    if out is None:
+        k_exp = torch.empty((p.batch, p.kv_heads, n_exp, p.head_dim), dtype=p.torch_dtype, device=dev)
+        v_exp = torch.empty_like(k_exp)
+        pos = torch.empty((p.batch, p.kv_heads, n_exp), dtype=torch.int32, device=dev)
+    else:
+        k_exp, v_exp, pos = out
+    has = n_tbm > 0
+    cp = p.c()
+    rc = lib().ems_expand(C.byref(cp), _ptr(merged["k_out"]), _ptr(merged["v_out"]),
+                          _ptr(merged["kept_pos"]), _ptr(tbm_idx) if has else None,
+                          _ptr(merged["tbm_dest"]) if has else None, _ptr(merged["k_norm"]),
+                          _ptr(k_exp), _ptr(v_exp), _ptr(pos), _stream())
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_expand")
+    return k_exp, v_exp, pos

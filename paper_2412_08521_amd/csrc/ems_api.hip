@@ -261,4 +261,24 @@ int ems_evict_merge(const ems_params* p, const void* k, const void* v,
     return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
 }
 
+int ems_expand(const ems_params* p, const void* k_cache, const void* v_cache,
+               const int32_t* kept_pos, const int32_t* tbm_idx, const int32_t* tbm_dest,
+               const float* k_norm, void* k_exp, void* v_exp, int32_t* pos_exp,
+               void* hip_stream)
+{
+    int why;
+    if (!full_params_ok(p, &why)) return why;
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+    if (!k_cache || !v_cache || !kept_pos || !k_norm || !k_exp || !v_exp || !pos_exp) return EMS_ERR_INVALID_ARG;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest)) return EMS_ERR_INVALID_ARG;
+    ems::ExpandArgs a{};
+    a.k_cache = k_cache; a.v_cache = v_cache; a.kept_pos = kept_pos; a.tbm_idx = tbm_idx;
+    a.tbm_dest = tbm_dest; a.k_norm = k_norm; a.k_exp = k_exp; a.v_exp = v_exp; a.pos_exp = pos_exp;
+    a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.window = p->window;
+    a.budget = p->budget; a.n_imp = n_imp; a.n_tbm = n_tbm;
+    const hipError_t e = ems::launch_expand(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -51,7 +51,21 @@ struct MergeArgs {
     float tau;
 };
 
+struct ExpandArgs {
+    const void* k_cache;
+    const void* v_cache;
+    const int32_t* kept_pos;
+    const int32_t* tbm_idx;
+    const int32_t* tbm_dest;
+    const float* k_norm;
+    void* k_exp;
+    void* v_exp;
+    int32_t* pos_exp;
+    int bkv, head_dim, window, budget, n_imp, n_tbm;
+};
+
 int score_keys_per_block(int dtype_is_f32);
+hipError_t launch_expand(const ExpandArgs& a, bool f32, hipStream_t st);
 hipError_t launch_score_pass1(const ScoreArgs& a, bool f32, hipStream_t st);   // rows' log-sum-exp
 hipError_t launch_score_pass2(const ScoreArgs& a, bool f32, hipStream_t st);   // column sums
 hipError_t launch_select(const SelectArgs& a, hipStream_t st);

@@ -353,6 +353,83 @@ __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Shared-entry expansion (App. A): one 16-lane group per output row; a merged token's key
+// is its entry's key rescaled from the centre's norm to the token's own norm.
+// ------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kMrgBlock) void expand_kernel(ExpandArgs a)
+{
+    using Acc = RowAcc<T, D>;
+    constexpr int kE = Acc::kE, kLpr = Acc::kLpr, kGroups = Acc::kGroups;
+    const int n_imp = a.n_imp, n_tbm = a.n_tbm, Nb = a.budget;
+    const int n_exp = n_imp + n_tbm + a.window;
+    const int bkv = blockIdx.y;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int grp = lane / kLpr, piece = lane % kLpr;
+    const int row = (blockIdx.x * kMrgWaves + wave) * kGroups + grp;
+    if (row >= n_exp) return;
+
+    const char* Kc = reinterpret_cast<const char*>(a.k_cache) + (size_t)bkv * (Nb + 1) * D * sizeof(T);
+    const char* Vc = reinterpret_cast<const char*>(a.v_cache) + (size_t)bkv * (Nb + 1) * D * sizeof(T);
+    char* Ke = reinterpret_cast<char*>(a.k_exp) + ((size_t)bkv * n_exp + row) * D * sizeof(T);
+    char* Ve = reinterpret_cast<char*>(a.v_exp) + ((size_t)bkv * n_exp + row) * D * sizeof(T);
+
+    int src = -1, pos = -1;          // cache row the token lives in
+    float scale = 1.f;
+    bool rescale = false;
+    if (row < n_imp) {
+        src = row; pos = a.kept_pos[(size_t)bkv * Nb + row];
+    } else if (row < n_imp + n_tbm) {
+        const int i = row - n_imp;
+        const int s = a.tbm_dest[(size_t)bkv * n_tbm + i];
+        if (s >= 0 && s < n_imp) {
+            const float nc = a.k_norm[(size_t)bkv * (n_imp + n_tbm) + s];
+            const float ni = a.k_norm[(size_t)bkv * (n_imp + n_tbm) + n_imp + i];
+            src = s; pos = a.tbm_idx[(size_t)bkv * n_tbm + i];
+            scale = nc > 0.f ? ni / nc : 0.f;
+            rescale = true;
+        }
+    } else {
+        src = n_imp + (row - n_imp - n_tbm); pos = a.kept_pos[(size_t)bkv * Nb + src];
+    }
+    frag_t fk = zero_frag(), fv = zero_frag();
+    if (src >= 0) {
+        fk = *reinterpret_cast<const frag_t*>(Kc + ((size_t)src * kLpr + piece) * 16);
+        fv = *reinterpret_cast<const frag_t*>(Vc + ((size_t)src * kLpr + piece) * 16);
+        if (rescale) {
+            float x[kE];
+            Pack<T>::unpack(fk, x);
+#pragma unroll
+            for (int e = 0; e < kE; ++e) x[e] *= scale;
+            fk = Pack<T>::pack(x);
+        }
+    }
+    *reinterpret_cast<frag_t*>(Ke + piece * 16) = fk;
+    *reinterpret_cast<frag_t*>(Ve + piece * 16) = fv;
+    if (piece == 0) a.pos_exp[(size_t)bkv * n_exp + row] = pos;
+}
+
+template <typename T, int D>
+static hipError_t launch_expand_t(const ExpandArgs& a, hipStream_t st)
+{
+    const int rows_per_block = kMrgWaves * RowAcc<T, D>::kGroups;
+    const int n_exp = a.n_imp + a.n_tbm + a.window;
+    dim3 g((n_exp + rows_per_block - 1) / rows_per_block, a.bkv);
+    hipLaunchKernelGGL((expand_kernel<T, D>), g, dim3(kMrgBlock), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand(const ExpandArgs& a, bool f32, hipStream_t st)
+{
+    if (f32) {
+        if (a.head_dim == 64) return launch_expand_t<float, 64>(a, st);
+        return launch_expand_t<float, 128>(a, st);
+    }
+    if (a.head_dim == 64) return launch_expand_t<bf16_t, 64>(a, st);
+    return launch_expand_t<bf16_t, 128>(a, st);
+}
+
 template <typename T, int D>
 static hipError_t launch_evict_merge_t(const MergeArgs& a, hipStream_t st)
 {

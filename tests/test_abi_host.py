@@ -103,3 +103,7 @@ def test_null_pointers_and_workspace_errors(lib):
     assert lib.ems_evict_merge(C.byref(cp), *args, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_evict_merge(C.byref(cp), *([d] * 12), 8, None) == B.EMS_ERR_WORKSPACE
     assert lib.ems_workspace_bytes(None, None, None, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_expand(C.byref(cp), d, d, d, d, d, None, d, d, d, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_expand(C.byref(cp), d, d, d, None, d, d, d, d, d, None) == B.EMS_ERR_INVALID_ARG
+    bad = _bad(budget=16).c()
+    assert lib.ems_expand(C.byref(bad), d, d, d, d, d, d, d, d, d, None) == B.EMS_ERR_INVALID_ARG

@@ -319,3 +319,47 @@ def test_score_split_calls_match_fused_call(mode):
     g3, l3 = B.ems_global_local_score_from_lse(p, q, k, torch.from_numpy(o_lse.astype(np.float32)).cuda())
     assert_rel(g3.cpu().numpy(), o_glo, max(RTOL[mode], 2e-5), "s_glo from oracle lse")
     assert_rel(l3.cpu().numpy(), o_loc, max(RTOL[mode], 2e-5), "s_loc from oracle lse")
+
+
+# ---------------------------------------------------------------------------- expansion
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("tau", [0.6, -2.0, 2.0])
+@pytest.mark.parametrize("shape", MERGE_SHAPES[:3])
+def test_expand_matches_oracle(shape, tau, mode):
+    """Shared-entry expansion of the GPU's own compact cache against the oracle's expansion
+    of the same cache (App. A): positions exact, keys/values to the rounding of one product."""
+    b, hkv, d, n, w, nb, r = shape
+    _log("expand", shape, "tau", tau, "mode", mode)
+    inp = ems_inputs.small(b, hkv, hkv, d, n, seed=nb + 7)
+    p = B.EmsParams(b, hkv, hkv, d, n, w, nb, merge_ratio=r, tau=tau, dtype=mode)
+    imp, tbm = _random_partition(p, seed=nb + 2)
+    kf = inp.f32("k").copy()
+    rng = np.random.default_rng(5)
+    for bb in range(b):
+        for h in range(hkv):
+            for t in tbm[bb, h, ::4]:
+                c = imp[bb, h, rng.integers(0, imp.shape[-1])]
+                kf[bb, h, t] = 0.9 * kf[bb, h, c] + 0.4 * kf[bb, h, t]
+    inp.k = ems_inputs.f32_to_bf16_bits(kf)
+    tbm_d = torch.from_numpy(tbm).cuda()
+    merged = B.ems_evict_merge(p, dev_tensor(inp.k, mode), dev_tensor(inp.v, mode),
+                               torch.from_numpy(imp).cuda(), tbm_d)
+    k_exp, v_exp, pos = B.ems_expand(p, merged, tbm_d)
+    host = {k_: (v_.float().cpu().numpy() if v_.is_floating_point() else v_.cpu().numpy())
+            for k_, v_ in merged.items()}
+    ko, vo, po = ems_ref.expand(ref_params(p), host["k_out"], host["v_out"], host["kept_pos"], tbm,
+                                host["tbm_dest"], host["k_norm"])
+    np.testing.assert_array_equal(pos.cpu().numpy(), po)
+    np.testing.assert_array_equal(v_exp.float().cpu().numpy(), vo)            # values are copies
+    got = k_exp.float().cpu().numpy()
+    rtol = 2.0 ** -8 if mode == B.EMS_BF16 else 1e-6                          # one rounding of n/n_c * k
+    rms = np.sqrt((ko ** 2).mean(-1, keepdims=True))
+    err = np.abs(got - ko) / np.maximum(np.abs(ko), 1e-2 * np.maximum(rms, 1e-30))
+    assert err.max() <= rtol, err.max()
+    n_imp, n_tbm = B.ems_partition_sizes(p)
+    assert k_exp.shape == (b, hkv, n_imp + n_tbm + w, d)
+    if tau >= 1:
+        assert (pos[..., n_imp:n_imp + n_tbm] == -1).all()
+    if tau == 0.6:
+        sel = pos[..., n_imp:n_imp + n_tbm]
+        assert (sel == -1).any() and (sel >= 0).any()
