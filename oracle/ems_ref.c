@@ -400,6 +400,149 @@ int ems_ref_evict_merge(const ems_ref_params* p, const float* k, const float* v,
 }
 
 /* ------------------------------------------------------------------------------------
+ * Sec. 4.1 "Redundancy" and the similarity ablation of App. B: the redundancy R[i][d] that
+ * Eq. 5 maximises is the key cosine, the value cosine, or -- the paper's own definition --
+ * the product of the two.  similarity: 0 = key, 1 = value, 2 = key x value.  A vector of
+ * norm 0 has cosine 0 to everything.  Threshold and tie-break as in ems_ref_dest; k_norm
+ * always holds KEY norms.
+ * ---------------------------------------------------------------------------------- */
+static double cosine(const float* a, const float* b, long D)
+{
+    const double na = l2norm(a, D), nb = l2norm(b, D);
+    if (!(na > 0.0) || !(nb > 0.0)) return 0.0;
+    double dot = 0.0;
+    for (long d = 0; d < D; ++d) dot += ((double)a[d] / na) * ((double)b[d] / nb);
+    return dot;
+}
+
+int ems_ref_dest_sim(const ems_ref_params* p, int similarity, const float* k, const float* v,
+                     const int32_t* imp_idx, const int32_t* tbm_idx,
+                     int32_t* tbm_dest, double* tbm_sim, double* k_norm_opt)
+{
+    int32_t n_imp, n_tbm;
+    if (ems_ref_sizes(p, &n_imp, &n_tbm) != REF_OK || !k || !v || !imp_idx) return REF_BAD;
+    if (similarity < 0 || similarity > 2) return REF_BAD;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest || !tbm_sim)) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len, D = p->head_dim;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < BH; ++u) {
+        const float* Ku = k + u * N * D;
+        const float* Vu = v + u * N * D;
+        const int32_t* imp = imp_idx + u * n_imp;
+        const int32_t* tbm = tbm_idx ? tbm_idx + u * n_tbm : NULL;
+        if (k_norm_opt) {
+            for (long c = 0; c < n_imp; ++c)
+                k_norm_opt[u * (n_imp + n_tbm) + c] = l2norm(Ku + (long)imp[c] * D, D);
+            for (long i = 0; i < n_tbm; ++i)
+                k_norm_opt[u * (n_imp + n_tbm) + n_imp + i] = l2norm(Ku + (long)tbm[i] * D, D);
+        }
+        for (long i = 0; i < n_tbm; ++i) {
+            double best = -INFINITY;
+            int32_t arg = 0;
+            for (long c = 0; c < n_imp; ++c) {
+                const double ck = cosine(Ku + (long)tbm[i] * D, Ku + (long)imp[c] * D, D);
+                const double cv = cosine(Vu + (long)tbm[i] * D, Vu + (long)imp[c] * D, D);
+                const double r = similarity == 0 ? ck : similarity == 1 ? cv : ck * cv;
+                if (r > best) { best = r; arg = (int32_t)c; }
+            }
+            tbm_sim[u * n_tbm + i] = best;
+            tbm_dest[u * n_tbm + i] = best > p->tau ? arg : p->budget;
+        }
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Sec. 4.2, last paragraph: the merge is weighted by the tokens' attention scores so that
+ * the more relevant members dominate.  `weight` is one non-negative score per token
+ * ([B,Hkv,N]; negative entries count as 0).  With w_i the weight of member i of an entry
+ * (centre included):
+ *     value = sum w_i v_i / sum w_i ,   key = n_centre * sum w_i (k_i/|k_i|) / sum w_i .
+ * An entry nobody joined, or whose weights add up to 0, stays the centre itself; a zero
+ * class whose weights add up to 0 is a zero row.  slot_count still counts members.
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_merge_weighted(const ems_ref_params* p, const float* k, const float* v,
+                           const double* weight,
+                           const int32_t* imp_idx, const int32_t* tbm_idx,
+                           const int32_t* tbm_dest,
+                           double* k_out, double* v_out, int32_t* kept_pos, int32_t* slot_count)
+{
+    int32_t n_imp, n_tbm;
+    if (ems_ref_sizes(p, &n_imp, &n_tbm) != REF_OK) return REF_BAD;
+    if (!k || !v || !weight || !imp_idx || !k_out || !v_out || !kept_pos || !slot_count) return REF_BAD;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest)) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len, D = p->head_dim;
+    const long Nb = p->budget, W = p->window, rows = Nb + 1;
+    for (long u = 0; u < BH; ++u)
+        for (long i = 0; i < n_tbm; ++i) {
+            const int32_t d = tbm_dest[u * n_tbm + i];
+            if (!((d >= 0 && d < n_imp) || d == Nb)) return REF_BAD;
+        }
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < BH; ++u) {
+        const float* Ku = k + u * N * D;
+        const float* Vu = v + u * N * D;
+        const double* Wu = weight + u * N;
+        const int32_t* imp = imp_idx + u * n_imp;
+        const int32_t* tbm = tbm_idx ? tbm_idx + u * n_tbm : NULL;
+        const int32_t* dst = tbm_dest ? tbm_dest + u * n_tbm : NULL;
+        double* Ko = k_out + u * rows * D;
+        double* Vo = v_out + u * rows * D;
+
+        for (long s = 0; s <= n_imp; ++s) {
+            const int zero_class = (s == n_imp);
+            const long target = zero_class ? Nb : s;
+            double* ko = Ko + target * D;
+            double* vo = Vo + target * D;
+            for (long d = 0; d < D; ++d) { ko[d] = 0.0; vo[d] = 0.0; }
+            long members = 0;
+            double total = 0.0, centre_norm = 1.0;
+            /* member list: the centre first (if any), then the TBM tokens in order */
+            for (long i = zero_class ? 0 : -1; i < n_tbm; ++i) {
+                long pos;
+                if (i < 0) pos = imp[s];
+                else if (dst[i] == target) pos = tbm[i];
+                else continue;
+                const double ni = l2norm(Ku + pos * D, D);
+                if (i < 0) centre_norm = ni;
+                const double w = Wu[pos] > 0.0 ? Wu[pos] : 0.0;
+                for (long d = 0; d < D; ++d) {
+                    ko[d] += ni > 0.0 ? w * ((double)Ku[pos * D + d] / ni) : 0.0;
+                    vo[d] += w * (double)Vu[pos * D + d];
+                }
+                total += w;
+                ++members;
+            }
+            slot_count[u * (n_imp + 1) + s] = (int32_t)members;
+            if (!zero_class && (members == 1 || !(total > 0.0))) {
+                for (long d = 0; d < D; ++d) {
+                    ko[d] = (double)Ku[(long)imp[s] * D + d];
+                    vo[d] = (double)Vu[(long)imp[s] * D + d];
+                }
+            } else if (total > 0.0) {
+                for (long d = 0; d < D; ++d) {
+                    ko[d] = centre_norm * (ko[d] / total);
+                    vo[d] = vo[d] / total;
+                }
+            } else {
+                for (long d = 0; d < D; ++d) { ko[d] = 0.0; vo[d] = 0.0; }
+            }
+        }
+        for (long s = 0; s < n_imp; ++s) kept_pos[u * Nb + s] = imp[s];
+        for (long t = 0; t < W; ++t) {
+            const long pos = N - W + t;
+            kept_pos[u * Nb + n_imp + t] = (int32_t)pos;
+            for (long d = 0; d < D; ++d) {
+                Ko[(n_imp + t) * D + d] = (double)Ku[pos * D + d];
+                Vo[(n_imp + t) * D + d] = (double)Vu[pos * D + d];
+            }
+        }
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------
  * App. A, "Shared Entry Expansion": tokens that were merged share one cache entry; at
  * compute time the entry is expanded back to one key/value per token with the help of
  * the look-up-table (which entry each token went to) and the stored key norms (Sec. 4.2:

@@ -84,6 +84,22 @@ int ems_ref_evict_merge(const ems_ref_params* p, const float* k, const float* v,
                         int32_t* tbm_dest, double* tbm_sim, double* k_norm_opt,
                         int32_t* slot_count);
 
+/* Eq. 5 with the redundancy of Sec. 4.1 / the similarity ablation of App. B:
+ * similarity 0 = key cosine (same as ems_ref_dest), 1 = value cosine, 2 = their product.
+ * k_norm_opt holds key norms in every mode. */
+int ems_ref_dest_sim(const ems_ref_params* p, int similarity, const float* k, const float* v,
+                     const int32_t* imp_idx, const int32_t* tbm_idx,
+                     int32_t* tbm_dest, double* tbm_sim, double* k_norm_opt);
+
+/* Score-weighted merge (Sec. 4.2, last paragraph): as ems_ref_merge with every member
+ * weighted by weight[pos] >= 0 ([B,Hkv,N] fp64; negatives count as 0).  An entry whose
+ * weights add up to 0 keeps its centre; a zero class of total weight 0 is a zero row. */
+int ems_ref_merge_weighted(const ems_ref_params* p, const float* k, const float* v,
+                           const double* weight,
+                           const int32_t* imp_idx, const int32_t* tbm_idx,
+                           const int32_t* tbm_dest,
+                           double* k_out, double* v_out, int32_t* kept_pos, int32_t* slot_count);
+
 /* Shared-entry expansion (App. A, "Shared Entry Expansion"; the position look-up-table of
  * Sec. 4.2): every kept token gets its run-time key and value back from its entry.
  * Row order per head: the N_imp centres, the N_tbm to-be-merged tokens (in tbm_idx order),

@@ -217,6 +217,47 @@ def evict_merge(p: RefParams, k, v, imp_idx, tbm_idx):
                 k_norm=norm, slot_count=cnt)
 
 
+def dest_sim(p: RefParams, similarity: int, k, v, imp_idx, tbm_idx):
+    k, v, imp_idx, tbm_idx = _f32(k), _f32(v), _i32(imp_idx), _i32(tbm_idx)
+    n_imp, n_tbm = sizes(p)
+    shape = (p.batch, p.kv_heads, p.seq_len, p.head_dim)
+    assert k.shape == shape and v.shape == shape
+    assert imp_idx.shape == (p.batch, p.kv_heads, n_imp)
+    assert tbm_idx.shape == (p.batch, p.kv_heads, n_tbm)
+    d = np.empty((p.batch, p.kv_heads, n_tbm), np.int32)
+    sim = np.empty((p.batch, p.kv_heads, n_tbm), np.float64)
+    norm = np.empty((p.batch, p.kv_heads, n_imp + n_tbm), np.float64)
+    cp = p.c()
+    _check(lib().ems_ref_dest_sim(C.byref(cp), C.c_int(int(similarity)), _ptr(k, C.c_float),
+                                  _ptr(v, C.c_float), _ptr(imp_idx, C.c_int32),
+                                  _ptr(tbm_idx, C.c_int32), _ptr(d, C.c_int32),
+                                  _ptr(sim, C.c_double), _ptr(norm, C.c_double)), "dest_sim")
+    return d, sim, norm
+
+
+def merge_weighted(p: RefParams, k, v, weight, imp_idx, tbm_idx, tbm_dest):
+    k, v, weight = _f32(k), _f32(v), _f64(weight)
+    imp_idx, tbm_idx, tbm_dest = _i32(imp_idx), _i32(tbm_idx), _i32(tbm_dest)
+    n_imp, n_tbm = sizes(p)
+    shape = (p.batch, p.kv_heads, p.seq_len, p.head_dim)
+    assert k.shape == shape and v.shape == shape and weight.shape == shape[:3]
+    assert imp_idx.shape == (p.batch, p.kv_heads, n_imp)
+    assert tbm_idx.shape == (p.batch, p.kv_heads, n_tbm)
+    assert tbm_dest.shape == (p.batch, p.kv_heads, n_tbm)
+    k_out = np.empty((p.batch, p.kv_heads, p.budget + 1, p.head_dim), np.float64)
+    v_out = np.empty_like(k_out)
+    kept = np.empty((p.batch, p.kv_heads, p.budget), np.int32)
+    cnt = np.empty((p.batch, p.kv_heads, n_imp + 1), np.int32)
+    cp = p.c()
+    _check(lib().ems_ref_merge_weighted(C.byref(cp), _ptr(k, C.c_float), _ptr(v, C.c_float),
+                                        _ptr(weight, C.c_double), _ptr(imp_idx, C.c_int32),
+                                        _ptr(tbm_idx, C.c_int32), _ptr(tbm_dest, C.c_int32),
+                                        _ptr(k_out, C.c_double), _ptr(v_out, C.c_double),
+                                        _ptr(kept, C.c_int32), _ptr(cnt, C.c_int32)),
+           "merge_weighted")
+    return k_out, v_out, kept, cnt
+
+
 def expand(p: RefParams, k_cache, v_cache, kept_pos, tbm_idx, tbm_dest, k_norm):
     k_cache, v_cache, k_norm = _f64(k_cache), _f64(v_cache), _f64(k_norm)
     kept_pos, tbm_idx, tbm_dest = _i32(kept_pos), _i32(tbm_idx), _i32(tbm_dest)
