@@ -48,6 +48,12 @@ typedef enum {
     EMS_F32 = 1    /* f32 I/O, f32 MFMA: the validation mode */
 } ems_dtype;
 
+typedef enum {
+    EMS_SIM_KEY = 0,       /* cosine of the keys */
+    EMS_SIM_VALUE = 1,     /* cosine of the values */
+    EMS_SIM_KEY_VALUE = 2  /* product of the two (the redundancy R of Sec. 4.1) */
+} ems_similarity;
+
 typedef struct {
     int32_t batch;         /* B  >= 1 */
     int32_t q_heads;       /* Hq >= 1 */
@@ -164,6 +170,29 @@ int ems_evict_merge(const ems_params* p, const void* k, const void* v,
                     int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
                     int32_t* slot_count,
                     void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * The paper-faithful variants of ems_evict_merge, same outputs and layouts:
+ *   similarity        an ems_similarity: the redundancy R[i][d] that Eq. 5 maximises and tau
+ *                     thresholds is the key cosine, the value cosine, or their product
+ *                     (Sec. 4.1 "Redundancy"; similarity ablation of App. B).  A vector of norm 0
+ *                     has cosine 0.  tbm_sim holds the winning R; k_norm holds key norms always.
+ *   token_weight_opt  in : device [B, Hkv, N] f32, or NULL.  When given, the merge is weighted
+ *                     by the tokens' attention scores (Sec. 4.2, last paragraph) -- e.g. the
+ *                     pooled Global-Local score of ems_select: with w_i = max(weight, 0) of
+ *                     member i (centre included), value = sum w_i v_i / sum w_i and key =
+ *                     n_centre * sum w_i (k_i/|k_i|) / sum w_i.  An entry nobody joined, or whose
+ *                     weights add up to 0, is a bit-exact copy of its centre; a zero class of
+ *                     total weight 0 is a zero row.  slot_count still counts members.
+ * With EMS_SIM_KEY and a NULL weight this is ems_evict_merge exactly.
+ */
+int ems_evict_merge_variant(const ems_params* p, int similarity, const void* k, const void* v,
+                            const float* token_weight_opt,
+                            const int32_t* imp_idx, const int32_t* tbm_idx,
+                            void* k_out, void* v_out, int32_t* kept_pos,
+                            int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
+                            int32_t* slot_count,
+                            void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Shared-entry expansion (App. A, "Shared Entry Expansion"; the position look-up-table of

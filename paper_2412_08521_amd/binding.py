@@ -22,10 +22,13 @@ EMS_ERR_WORKSPACE = -3
 EMS_ERR_LAUNCH = -4
 EMS_BF16 = 0
 EMS_F32 = 1
+EMS_SIM_KEY = 0
+EMS_SIM_VALUE = 1
+EMS_SIM_KEY_VALUE = 2
 
 EXPORTS = ("ems_version", "ems_strerror", "ems_partition_sizes", "ems_workspace_bytes",
            "ems_global_local_score", "ems_attention_lse", "ems_global_local_score_from_lse",
-           "ems_select", "ems_evict_merge", "ems_expand")
+           "ems_select", "ems_evict_merge", "ems_evict_merge_variant", "ems_expand")
 
 
 class ems_params(C.Structure):
@@ -87,6 +90,7 @@ def lib():
         l.ems_global_local_score_from_lse.argtypes = [P] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         l.ems_select.argtypes = [P] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         l.ems_evict_merge.argtypes = [P] + [C.c_void_p] * 12 + [C.c_size_t, C.c_void_p]
+        l.ems_evict_merge_variant.argtypes = ([P, C.c_int] + [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p])
         l.ems_expand.argtypes = [P] + [C.c_void_p] * 10
         for name in EXPORTS[2:]:
             getattr(l, name).restype = C.c_int
@@ -258,6 +262,33 @@ def ems_evict_merge(p: EmsParams, k, v, imp_idx, tbm_idx, ws=None, out=None):
                                _ptr(o["slot_count"]), _ptr(ws), ws.numel(), _stream())
     if rc != EMS_OK:
         raise EmsError(rc, "ems_evict_merge")
+    return o
+
+
+def ems_evict_merge_variant(p: EmsParams, similarity: int, k, v, token_weight, imp_idx, tbm_idx,
+                            ws=None, out=None):
+    """ems_evict_merge with the redundancy of `similarity` (EMS_SIM_*) and, when `token_weight`
+    ([B, Hkv, N] f32) is given, the score-weighted merge.  Same outputs."""
+    shape = (p.batch, p.kv_heads, p.seq_len, p.head_dim)
+    _check_tensor(k, shape, p.torch_dtype, "k")
+    _check_tensor(v, shape, p.torch_dtype, "v")
+    if token_weight is not None:
+        _check_tensor(token_weight, shape[:3], torch.float32, "token_weight")
+    n_imp, n_tbm = ems_partition_sizes(p)
+    _check_tensor(imp_idx, (p.batch, p.kv_heads, n_imp), torch.int32, "imp_idx")
+    _check_tensor(tbm_idx, (p.batch, p.kv_heads, n_tbm), torch.int32, "tbm_idx")
+    dev = k.device
+    ws = _workspace(ems_workspace_bytes(p)[2], dev, ws)
+    o = out if out is not None else alloc_evict_merge_outputs(p, dev)
+    has = n_tbm > 0
+    cp = p.c()
+    rc = lib().ems_evict_merge_variant(
+        C.byref(cp), int(similarity), _ptr(k), _ptr(v), _ptr(token_weight), _ptr(imp_idx),
+        _ptr(tbm_idx) if has else None, _ptr(o["k_out"]), _ptr(o["v_out"]), _ptr(o["kept_pos"]),
+        _ptr(o["tbm_dest"]) if has else None, _ptr(o["tbm_sim"]) if has else None,
+        _ptr(o["k_norm"]), _ptr(o["slot_count"]), _ptr(ws), ws.numel(), _stream())
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_evict_merge_variant")
     return o
 
 

@@ -240,8 +240,22 @@ int ems_evict_merge(const ems_params* p, const void* k, const void* v,
                     int32_t* slot_count,
                     void* ws, size_t ws_bytes, void* hip_stream)
 {
+    return ems_evict_merge_variant(p, EMS_SIM_KEY, k, v, nullptr, imp_idx, tbm_idx, k_out, v_out, kept_pos,
+                                   tbm_dest, tbm_sim, k_norm_opt, slot_count, ws, ws_bytes, hip_stream);
+}
+
+int ems_evict_merge_variant(const ems_params* p, int similarity, const void* k, const void* v,
+                            const float* token_weight_opt,
+                            const int32_t* imp_idx, const int32_t* tbm_idx,
+                            void* k_out, void* v_out, int32_t* kept_pos,
+                            int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
+                            int32_t* slot_count,
+                            void* ws, size_t ws_bytes, void* hip_stream)
+{
     int why;
     if (!full_params_ok(p, &why)) return why;
+    if (similarity != EMS_SIM_KEY && similarity != EMS_SIM_VALUE && similarity != EMS_SIM_KEY_VALUE)
+        return EMS_ERR_INVALID_ARG;
     int n_imp, n_tbm;
     partition_sizes(p, &n_imp, &n_tbm);
     if (!k || !v || !imp_idx || !k_out || !v_out || !kept_pos || !slot_count) return EMS_ERR_INVALID_ARG;
@@ -257,6 +271,7 @@ int ems_evict_merge(const ems_params* p, const void* k, const void* v,
     a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len;
     a.window = p->window; a.budget = p->budget; a.n_imp = n_imp; a.n_tbm = n_tbm;
     a.tau = p->tau;
+    a.weight = token_weight_opt; a.similarity = similarity;
     const hipError_t e = ems::launch_evict_merge(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
 }

@@ -49,6 +49,8 @@ struct MergeArgs {
     int32_t* slot_count;
     int bkv, head_dim, seq_len, window, budget, n_imp, n_tbm;
     float tau;
+    const float* weight;  // [B*Hkv, seq_len] per-token merge weight, or null = plain mean
+    int similarity;       // 0 key cosine, 1 value cosine, 2 their product
 };
 
 struct ExpandArgs {

@@ -44,12 +44,14 @@ template <> __device__ __forceinline__ float frag_sumsq<float>(const frag_t& f)
 __device__ __forceinline__ float inv_norm(float sumsq) { return sumsq > 0.f ? 1.0f / sqrtf(sumsq) : 0.f; }
 
 // ------------------------------------------------------------------------------------
-// Destination of every TBM token (Eq. 5 with key-cosine similarity, then the threshold).
-// Block = (128 TBM tokens, one (b, kv-head)); each wave keeps 32 TBM keys in registers as
-// the MFMA B operand (tokens -> lanes) and the centre keys stream through LDS as the A
+// Destination of every TBM token (Eq. 5, then the threshold).  The redundancy is the key
+// cosine, the value cosine or their product (Sec. 4.1; similarity ablation of App. B):
+// kSim = 0 / 1 / 2, i.e. one or two sources, each with its own MFMA contraction.
+// Block = (128 TBM tokens, one (b, kv-head)); each wave keeps 32 TBM rows in registers as
+// the MFMA B operand (tokens -> lanes) and the centre rows stream through LDS as the A
 // operand (centres -> accumulator registers), so the running arg-max is a per-lane pair.
 // ------------------------------------------------------------------------------------
-template <typename T, int D>
+template <typename T, int D, int kSim>
 __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
 {
     constexpr int kStageRows = DestCfg<T>::kStageRows;
@@ -57,13 +59,19 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
     constexpr int kStride = Tile<T, D>::kLdsStride;
     constexpr int kCpr = Tile<T, D>::kChunksPerRow;
     constexpr int kPerThread = kCpr * kStageRows / kMrgBlock;
+    constexpr int kSrc = kSim == 2 ? 2 : 1;
 
-    __shared__ __attribute__((aligned(16))) char lds[kStageRows * kStride];
-    __shared__ __attribute__((aligned(16))) float lds_rn[kStageRows];
+    __shared__ __attribute__((aligned(16))) char lds[kSrc][kStageRows * kStride];
+    __shared__ __attribute__((aligned(16))) float lds_rn[kSrc][kStageRows];
 
     const int N = a.seq_len, n_imp = a.n_imp, n_tbm = a.n_tbm;
     const int bkv = blockIdx.y;
     const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
+    const T* V = reinterpret_cast<const T*>(a.v) + ((size_t)bkv * N) * D;
+    const T* src[kSrc];
+    if constexpr (kSim == 0) { src[0] = K; }
+    else if constexpr (kSim == 1) { src[0] = V; }
+    else { src[0] = K; src[1] = V; }
     const int32_t* imp = a.imp_idx + (size_t)bkv * n_imp;
     const int32_t* tbm = a.tbm_idx + (size_t)bkv * n_tbm;
 
@@ -73,15 +81,27 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
     const bool t_ok = ti < n_tbm;
     const int t_pos = t_ok ? clamp_pos(tbm[ti], N) : 0;
 
-    frag_t bt[kFrags];
-    float t_sumsq = 0.f;
+    frag_t bt[kSrc][kFrags];
+    float t_rn[kSrc];
+    float k_sumsq = 0.f;
 #pragma unroll
-    for (int f = 0; f < kFrags; ++f) {
-        bt[f] = load_frag_or_zero(K, (size_t)t_pos * Tile<T, D>::kRowBytes + f * 32 + half * 16, t_ok);
-        t_sumsq += frag_sumsq<T>(bt[f]);
+    for (int s = 0; s < kSrc; ++s) {
+        float ss = 0.f;
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f) {
+            bt[s][f] = load_frag_or_zero(src[s], (size_t)t_pos * Tile<T, D>::kRowBytes + f * 32 + half * 16, t_ok);
+            ss += frag_sumsq<T>(bt[s][f]);
+        }
+        ss += __shfl_xor(ss, 32);
+        t_rn[s] = inv_norm(ss);
+        if (kSim != 1 && s == 0) k_sumsq = ss;
     }
-    t_sumsq += __shfl_xor(t_sumsq, 32);
-    const float t_rn = inv_norm(t_sumsq);
+    if constexpr (kSim == 1) {                                      // the key norm is an output in every mode
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f)
+            k_sumsq += frag_sumsq<T>(load_frag_or_zero(K, (size_t)t_pos * Tile<T, D>::kRowBytes + f * 32 + half * 16, t_ok));
+        k_sumsq += __shfl_xor(k_sumsq, 32);
+    }
 
     float best = -INFINITY;
     int arg = 0;
@@ -95,32 +115,43 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
             const int ci = c0 + row;
             const bool ok = ci < n_imp;
             const int pos = ok ? clamp_pos(imp[ci], N) : 0;
-            const frag_t v = load_frag_or_zero(K, ((size_t)pos * kCpr + cc) * 16, ok);
-            *reinterpret_cast<frag_t*>(lds + row * kStride + cc * 16) = v;
-            // the kCpr consecutive lanes that hold one row add up its squares
-            float ss = frag_sumsq<T>(v);
 #pragma unroll
-            for (int o = kCpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
-            if (cc == 0) lds_rn[row] = inv_norm(ss);
+            for (int s = 0; s < kSrc; ++s) {
+                const frag_t v = load_frag_or_zero(src[s], ((size_t)pos * kCpr + cc) * 16, ok);
+                *reinterpret_cast<frag_t*>(lds[s] + row * kStride + cc * 16) = v;
+                // the kCpr consecutive lanes that hold one row add up its squares
+                float ss = frag_sumsq<T>(v);
+#pragma unroll
+                for (int o = kCpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+                if (cc == 0) lds_rn[s][row] = inv_norm(ss);
+            }
         }
         __syncthreads();
 #pragma unroll
         for (int rs = 0; rs < kStageRows / 32; ++rs) {
             const int cbase = c0 + rs * 32;
             if (cbase >= n_imp) continue;                  // block-uniform
-            f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            f32x16_t acc[kSrc];
 #pragma unroll
-            for (int f = 0; f < kFrags; ++f) {
-                const frag_t ac = *reinterpret_cast<const frag_t*>(lds + (rs * 32 + col) * kStride + f * 32 + half * 16);
-                mma<T>(acc, ac, bt[f]);
+            for (int s = 0; s < kSrc; ++s) {
+                acc[s] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < kFrags; ++f) {
+                    const frag_t ac = *reinterpret_cast<const frag_t*>(lds[s] + (rs * 32 + col) * kStride + f * 32 + half * 16);
+                    mma<T>(acc[s], ac, bt[s][f]);
+                }
             }
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4_t rn = *reinterpret_cast<const f32x4_t*>(lds_rn + rs * 32 + 8 * q4 + 4 * half);
+                f32x4_t rn[kSrc];
+#pragma unroll
+                for (int s = 0; s < kSrc; ++s)
+                    rn[s] = *reinterpret_cast<const f32x4_t*>(lds_rn[s] + rs * 32 + 8 * q4 + 4 * half);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int ci = cbase + 8 * q4 + 4 * half + e;
-                    const float sim = (acc[4 * q4 + e] * rn[e]) * t_rn;
+                    float sim = (acc[0][4 * q4 + e] * rn[0][e]) * t_rn[0];
+                    if constexpr (kSrc == 2) sim *= (acc[1][4 * q4 + e] * rn[1][e]) * t_rn[1];
                     if (ci < n_imp && sim > best) { best = sim; arg = ci; }
                 }
             }
@@ -133,7 +164,7 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
     if (half == 0 && t_ok) {
         a.tbm_sim[(size_t)bkv * n_tbm + ti] = best;
         a.tbm_dest[(size_t)bkv * n_tbm + ti] = best > a.tau ? arg : a.budget;
-        a.k_norm[(size_t)bkv * (n_imp + n_tbm) + n_imp + ti] = sqrtf(t_sumsq);
+        a.k_norm[(size_t)bkv * (n_imp + n_tbm) + n_imp + ti] = sqrtf(k_sumsq);
     }
 }
 
@@ -182,10 +213,12 @@ struct RowAcc {
     static constexpr int kLpr = Tile<T, D>::kChunksPerRow;     // lanes per row
     static constexpr int kGroups = kWave / kLpr;
     float k[kE], v[kE];
+    float wsum;                                                // weighted merge only
     __device__ __forceinline__ void clear()
     {
 #pragma unroll
         for (int i = 0; i < kE; ++i) { k[i] = 0.f; v[i] = 0.f; }
+        wsum = 0.f;
     }
     // adds token `pos` (unit key, raw value); returns the key's norm.  All kLpr lanes of
     // the group must call together.
@@ -204,22 +237,41 @@ struct RowAcc {
         for (int i = 0; i < kE; ++i) { k[i] = __builtin_fmaf(xk[i], rn, k[i]); v[i] += xv[i]; }
         return sqrtf(ss);
     }
+    // the same with weight w >= 0 on the token (score-weighted merge, Sec. 4.2)
+    __device__ __forceinline__ float add_weighted(const T* K, const T* V, int pos, int piece, float w)
+    {
+        const frag_t fk = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)pos * kLpr + piece) * 16);
+        const frag_t fv = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)pos * kLpr + piece) * 16);
+        float ss = frag_sumsq<T>(fk);
+#pragma unroll
+        for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        const float rnw = inv_norm(ss) * w;
+        float xk[kE], xv[kE];
+        Pack<T>::unpack(fk, xk);
+        Pack<T>::unpack(fv, xv);
+#pragma unroll
+        for (int i = 0; i < kE; ++i) { k[i] = __builtin_fmaf(xk[i], rnw, k[i]); v[i] = __builtin_fmaf(xv[i], w, v[i]); }
+        wsum += w;
+        return sqrtf(ss);
+    }
     // adds the groups together: afterwards every group holds the total
+    template <bool kWeighted>
     __device__ __forceinline__ void reduce_groups()
     {
 #pragma unroll
         for (int o = kLpr; o < kWave; o <<= 1) {
 #pragma unroll
             for (int i = 0; i < kE; ++i) { k[i] += __shfl_xor(k[i], o); v[i] += __shfl_xor(v[i], o); }
+            if constexpr (kWeighted) wsum += __shfl_xor(wsum, o);
         }
     }
 };
 
 // Walks the TBM tokens of chunks `first, first+step, ...` (64 tokens each) whose
 // destination is `target` and adds them to `acc`; returns how many there were.
-template <typename T, int D>
+template <typename T, int D, bool kWeighted>
 __device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const MergeArgs& a, const T* K, const T* V,
-                                              const int32_t* tbm, const int32_t* dest, int target,
+                                              const float* Wt, const int32_t* tbm, const int32_t* dest, int target,
                                               int first, int step, int* wlist)
 {
     constexpr int kLpr = RowAcc<T, D>::kLpr, kGroups = RowAcc<T, D>::kGroups;
@@ -238,7 +290,10 @@ __device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const MergeArgs
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         for (int m0 = 0; m0 < n; m0 += kGroups) {
             const int m = m0 + grp;
-            if (m < n) acc.add(K, V, wlist[m], piece);
+            if (m < n) {
+                if constexpr (kWeighted) acc.add_weighted(K, V, wlist[m], piece, fmaxf(Wt[wlist[m]], 0.f));
+                else acc.add(K, V, wlist[m], piece);
+            }
         }
         __builtin_amdgcn_wave_barrier();
         count += n;
@@ -246,7 +301,7 @@ __device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const MergeArgs
     return count;
 }
 
-template <typename T, int D>
+template <typename T, int D, bool kWeighted>
 __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
 {
     using Acc = RowAcc<T, D>;
@@ -255,6 +310,7 @@ __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
     __shared__ int wlist_all[kMrgWaves][kWave];
     __shared__ float zsum[kMrgWaves][2][D];
     __shared__ int zcnt[kMrgWaves];
+    __shared__ float zwsum[kMrgWaves];
 
     const int N = a.seq_len, W = a.window, Nb = a.budget, n_imp = a.n_imp, n_tbm = a.n_tbm;
     const int bkv = blockIdx.y;
@@ -267,6 +323,7 @@ __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
     const int32_t* dest = n_tbm ? a.tbm_dest + (size_t)bkv * n_tbm : nullptr;
     int32_t* kept = a.kept_pos + (size_t)bkv * Nb;
     int32_t* cnt = a.slot_count + (size_t)bkv * (n_imp + 1);
+    const float* Wt = kWeighted ? a.weight + (size_t)bkv * N : nullptr;
 
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int grp = lane / kLpr, piece = lane % kLpr;
@@ -275,26 +332,26 @@ __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
     if (blockIdx.x == 0) {
         // ---- zero class: the four waves split the TBM list, wave 0 adds them in order
         Acc acc; acc.clear();
-        const int n = gather_members<T, D>(acc, a, K, V, tbm, dest, Nb, wave, kMrgWaves, wlist);
-        acc.reduce_groups();
+        const int n = gather_members<T, D, kWeighted>(acc, a, K, V, Wt, tbm, dest, Nb, wave, kMrgWaves, wlist);
+        acc.template reduce_groups<kWeighted>();
         if (grp == 0) {
 #pragma unroll
             for (int i = 0; i < kE; ++i) { zsum[wave][0][piece * kE + i] = acc.k[i]; zsum[wave][1][piece * kE + i] = acc.v[i]; }
         }
-        if (lane == 0) zcnt[wave] = n;
+        if (lane == 0) { zcnt[wave] = n; zwsum[wave] = acc.wsum; }
         __syncthreads();
         if (wave == 0 && grp == 0) {
             int total = 0;
-            for (int w = 0; w < kMrgWaves; ++w) total += zcnt[w];
+            float wtot = 0.f;
+            for (int w = 0; w < kMrgWaves; ++w) { total += zcnt[w]; wtot += zwsum[w]; }
+            const float denom = kWeighted ? wtot : (float)total;     // members, or their total weight
             float ok[kE], ov[kE];
 #pragma unroll
             for (int i = 0; i < kE; ++i) {
                 float sk = 0.f, sv = 0.f;
                 for (int w = 0; w < kMrgWaves; ++w) { sk += zsum[w][0][piece * kE + i]; sv += zsum[w][1][piece * kE + i]; }
-                const float inv = total > 0 ? 1.0f / (float)total : 0.f;
-                ok[i] = total > 0 ? sk / (float)total : 0.f;
-                ov[i] = total > 0 ? sv / (float)total : 0.f;
-                (void)inv;
+                ok[i] = denom > 0.f ? sk / denom : 0.f;
+                ov[i] = denom > 0.f ? sv / denom : 0.f;
             }
             *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ok);
             *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ov);
@@ -328,16 +385,17 @@ __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
     if (grp == 0) {
         raw_k = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)c_pos * kLpr + piece) * 16);
         raw_v = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)c_pos * kLpr + piece) * 16);
-        c_norm = acc.add(K, V, c_pos, piece);
+        if constexpr (kWeighted) c_norm = acc.add_weighted(K, V, c_pos, piece, fmaxf(Wt[c_pos], 0.f));
+        else c_norm = acc.add(K, V, c_pos, piece);
     }
     c_norm = __shfl(c_norm, 0);
-    const int members = 1 + gather_members<T, D>(acc, a, K, V, tbm, dest, job, 0, 1, wlist);
-    acc.reduce_groups();
+    const int members = 1 + gather_members<T, D, kWeighted>(acc, a, K, V, Wt, tbm, dest, job, 0, 1, wlist);
+    acc.template reduce_groups<kWeighted>();
     if (grp == 0) {
         frag_t out_k = raw_k, out_v = raw_v;                      // nobody joined: exact copy
-        if (members > 1) {
+        const float m = kWeighted ? acc.wsum : (float)members;    // total weight of the entry
+        if (members > 1 && m > 0.f) {
             float ok[kE], ov[kE];
-            const float m = (float)members;
 #pragma unroll
             for (int i = 0; i < kE; ++i) { ok[i] = c_norm * (acc.k[i] / m); ov[i] = acc.v[i] / m; }
             out_k = Pack<T>::pack(ok);
@@ -436,13 +494,16 @@ static hipError_t launch_evict_merge_t(const MergeArgs& a, hipStream_t st)
     hipError_t e = hipSuccess;
     if (a.n_tbm > 0) {
         dim3 g((a.n_tbm + kMrgWaves * 32 - 1) / (kMrgWaves * 32), a.bkv);
-        hipLaunchKernelGGL((dest_kernel<T, D>), g, dim3(kMrgBlock), 0, st, a);
+        if (a.similarity == 0) hipLaunchKernelGGL((dest_kernel<T, D, 0>), g, dim3(kMrgBlock), 0, st, a);
+        else if (a.similarity == 1) hipLaunchKernelGGL((dest_kernel<T, D, 1>), g, dim3(kMrgBlock), 0, st, a);
+        else hipLaunchKernelGGL((dest_kernel<T, D, 2>), g, dim3(kMrgBlock), 0, st, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     const int jobs = a.n_imp + a.window;
     dim3 g(1 + (jobs + kMrgWaves - 1) / kMrgWaves, a.bkv);
-    hipLaunchKernelGGL((merge_kernel<T, D>), g, dim3(kMrgBlock), 0, st, a);
+    if (a.weight) hipLaunchKernelGGL((merge_kernel<T, D, true>), g, dim3(kMrgBlock), 0, st, a);
+    else hipLaunchKernelGGL((merge_kernel<T, D, false>), g, dim3(kMrgBlock), 0, st, a);
     return hipGetLastError();
 }
 

@@ -105,5 +105,10 @@ def test_null_pointers_and_workspace_errors(lib):
     assert lib.ems_workspace_bytes(None, None, None, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_expand(C.byref(cp), d, d, d, d, d, None, d, d, d, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_expand(C.byref(cp), d, d, d, None, d, d, d, d, d, None) == B.EMS_ERR_INVALID_ARG
+    args = [d] * 13 + [1 << 20, None]
+    assert lib.ems_evict_merge_variant(C.byref(cp), 3, *args) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_evict_merge_variant(C.byref(cp), -1, *args) == B.EMS_ERR_INVALID_ARG
+    args[0] = None
+    assert lib.ems_evict_merge_variant(C.byref(cp), 2, *args) == B.EMS_ERR_INVALID_ARG
     bad = _bad(budget=16).c()
     assert lib.ems_expand(C.byref(bad), d, d, d, d, d, d, d, d, d, None) == B.EMS_ERR_INVALID_ARG

@@ -363,3 +363,102 @@ def test_expand_matches_oracle(shape, tau, mode):
     if tau == 0.6:
         sel = pos[..., n_imp:n_imp + n_tbm]
         assert (sel == -1).any() and (sel >= 0).any()
+
+
+# ---------------------------------------------------------------------------- merge variants
+def _unit64(x):
+    x = x.astype(np.float64)
+    return x / np.linalg.norm(x, axis=-1, keepdims=True)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("weighted", [False, True])
+@pytest.mark.parametrize("sim", [B.EMS_SIM_KEY, B.EMS_SIM_VALUE, B.EMS_SIM_KEY_VALUE])
+@pytest.mark.parametrize("shape", MERGE_SHAPES[:3])
+def test_evict_merge_variant_matches_oracle(shape, sim, weighted, mode):
+    """Redundancy as key / value / key x value cosine (Sec. 4.1) and the score-weighted merge
+    (Sec. 4.2) against the oracle's versions of both."""
+    b, hkv, d, n, w, nb, r = shape
+    tau = 0.5
+    _log("variant", shape, "sim", sim, "weighted", weighted, "mode", mode)
+    inp = ems_inputs.small(b, hkv, hkv, d, n, seed=nb + 11)
+    p = B.EmsParams(b, hkv, hkv, d, n, w, nb, merge_ratio=r, tau=tau, dtype=mode)
+    imp, tbm = _random_partition(p, seed=nb + 5)
+    kf, vf = inp.f32("k").copy(), inp.f32("v").copy()
+    rng = np.random.default_rng(9)
+    for bb in range(b):
+        for h in range(hkv):
+            for t in tbm[bb, h, ::3]:                      # near-duplicates in keys AND values
+                c = imp[bb, h, rng.integers(0, imp.shape[-1])]
+                kf[bb, h, t] = 0.9 * kf[bb, h, c] + 0.3 * kf[bb, h, t]
+                vf[bb, h, t] = 0.8 * vf[bb, h, c] + 0.35 * vf[bb, h, t]
+    inp.k, inp.v = ems_inputs.f32_to_bf16_bits(kf), ems_inputs.f32_to_bf16_bits(vf)
+    kf, vf = inp.f32("k"), inp.f32("v")
+    wt = None
+    if weighted:
+        wt = rng.uniform(0.0, 2.0, (b, hkv, n)).astype(np.float32)
+        wt[..., ::7] = 0.0
+        wt[..., 3::11] = -0.5                               # counts as 0
+
+    out = B.ems_evict_merge_variant(p, sim, dev_tensor(inp.k, mode), dev_tensor(inp.v, mode),
+                                    None if wt is None else torch.from_numpy(wt).cuda(),
+                                    torch.from_numpy(imp).cuda(), torch.from_numpy(tbm).cuda())
+    out = {k_: v_.float().cpu().numpy() if v_.is_floating_point() else v_.cpu().numpy()
+           for k_, v_ in out.items()}
+    rp = ref_params(p)
+    d_ref, s_ref, n_ref = ems_ref.dest_sim(rp, sim, kf, vf, imp, tbm)
+    n_imp, n_tbm = B.ems_partition_sizes(p)
+    np.testing.assert_allclose(out["tbm_sim"], s_ref, rtol=0, atol=1e-5)
+    np.testing.assert_allclose(out["k_norm"], n_ref, rtol=1e-6)
+    differ = out["tbm_dest"] != d_ref
+    for bb, h, i in zip(*np.nonzero(differ)):
+        ck = _unit64(kf[bb, h, imp[bb, h]]) @ _unit64(kf[bb, h, tbm[bb, h, i]])
+        cv = _unit64(vf[bb, h, imp[bb, h]]) @ _unit64(vf[bb, h, tbm[bb, h, i]])
+        top2 = np.sort([ck, cv, ck * cv][sim])[-2:]
+        assert top2[1] - top2[0] < 4e-5 or abs(top2[1] - tau) < 4e-5, (bb, h, i, top2)
+    assert differ.mean() < 0.01
+    assert (out["tbm_dest"] < n_imp).any() and (out["tbm_dest"] == nb).any()
+
+    if weighted:
+        k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge_weighted(rp, kf, vf, wt, imp, tbm, out["tbm_dest"])
+    else:
+        k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge(rp, kf, vf, imp, tbm, out["tbm_dest"])
+    np.testing.assert_array_equal(out["kept_pos"], kept_ref)
+    np.testing.assert_array_equal(out["slot_count"], cnt_ref)
+    for name, got, want in (("k_out", out["k_out"], k_ref), ("v_out", out["v_out"], v_ref)):
+        rms = np.sqrt((want ** 2).mean(-1, keepdims=True))
+        err = np.abs(got - want) / np.maximum(np.abs(want), 1e-2 * np.maximum(rms, 1e-30))
+        assert err.max() <= RTOL_MERGE[mode], f"{name}: {err.max():.3e}"
+
+
+def test_variant_with_key_cosine_and_no_weights_is_evict_merge():
+    b, hkv, d, n, w, nb, r = MERGE_SHAPES[1]
+    inp = ems_inputs.small(b, hkv, hkv, d, n, seed=77)
+    p = B.EmsParams(b, hkv, hkv, d, n, w, nb, merge_ratio=r, tau=0.2)
+    imp, tbm = _random_partition(p, seed=78)
+    k, v = dev_tensor(inp.k, B.EMS_BF16), dev_tensor(inp.v, B.EMS_BF16)
+    i_d, t_d = torch.from_numpy(imp).cuda(), torch.from_numpy(tbm).cuda()
+    a = B.ems_evict_merge(p, k, v, i_d, t_d)
+    c = B.ems_evict_merge_variant(p, B.EMS_SIM_KEY, k, v, None, i_d, t_d)
+    for name in a:
+        assert torch.equal(a[name].view(torch.uint8), c[name].view(torch.uint8)), name
+    # constant weights: same destinations, same averages up to the rounding of the weights' products
+    ones = torch.full((b, hkv, n), 0.5, device="cuda")
+    e = B.ems_evict_merge_variant(p, B.EMS_SIM_KEY, k, v, ones, i_d, t_d)
+    assert torch.equal(a["tbm_dest"], e["tbm_dest"]) and torch.equal(a["slot_count"], e["slot_count"])
+    torch.testing.assert_close(e["v_out"].float(), a["v_out"].float(), rtol=2e-2, atol=1e-3)
+
+
+def test_all_zero_weights_keep_the_centres_on_gpu():
+    b, hkv, d, n, w, nb, r = MERGE_SHAPES[0]
+    inp = ems_inputs.small(b, hkv, hkv, d, n, seed=79)
+    p = B.EmsParams(b, hkv, hkv, d, n, w, nb, merge_ratio=r, tau=-2.0)
+    imp, tbm = _random_partition(p, seed=80)
+    k, v = dev_tensor(inp.k, B.EMS_BF16), dev_tensor(inp.v, B.EMS_BF16)
+    i_d, t_d = torch.from_numpy(imp).cuda(), torch.from_numpy(tbm).cuda()
+    o = B.ems_evict_merge_variant(p, B.EMS_SIM_KEY_VALUE, k, v, torch.zeros((b, hkv, n), device="cuda"), i_d, t_d)
+    n_imp, _ = B.ems_partition_sizes(p)
+    for h in range(hkv):
+        assert torch.equal(o["k_out"][0, h, :n_imp], k[0, h, i_d[0, h].long()])
+        assert torch.equal(o["v_out"][0, h, :n_imp], v[0, h, i_d[0, h].long()])
+    assert (o["slot_count"][..., :n_imp].sum(-1) == n_imp + (o["tbm_dest"] < n_imp).sum(-1)).all()
