@@ -36,6 +36,10 @@ def main():
     ap.add_argument("--f32", action="store_true", help="validation mode (f32 MFMA)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the timings of the entry points outside the headline step "
+                         "(expansion, merge variants, decode-time update)")
+    ap.add_argument("--decode-steps", type=int, default=64)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -171,6 +175,12 @@ def main():
         "roofline": roofline, "score_pass1": pass1,
     }
 
+    # ---- entry points outside the headline step, same shapes, reported on their own
+    if not args.no_extras:
+        result["extras_us"] = time_extras(args, p, w, B, torch, timed, k, v, s_glo, s_loc, imp, tbm,
+                                          outs, ws_select, ws_merge)
+        log(f"extras us: {result['extras_us']}")
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     if not args.no_cpu_baseline:
         from oracle import ems_ref
@@ -197,6 +207,50 @@ def main():
         log(f"cpu baseline: score {t_score:.2f}s rest {t_rest:.3f}s")
 
     print(json.dumps(result), flush=True)
+
+
+def time_extras(args, p, w, B, torch, timed, k, v, s_glo, s_loc, imp, tbm, merged, ws_select, ws_merge):
+    """Microseconds per call of ems_expand, ems_evict_merge_variant (key x value redundancy,
+    score-weighted), ems_decode_init and ems_decode_step (average over --decode-steps
+    consecutive generated tokens) on the workload's shapes; outputs allocated up front."""
+    K = args.steps
+    n_imp, n_tbm = B.ems_partition_sizes(p)
+    n_exp = n_imp + n_tbm + w.window
+    out = {}
+    k_exp = torch.empty((w.batch, w.kv_heads, n_exp, w.head_dim), dtype=p.torch_dtype, device="cuda")
+    v_exp = torch.empty_like(k_exp)
+    pos_exp = torch.empty((w.batch, w.kv_heads, n_exp), dtype=torch.int32, device="cuda")
+    out["expand"] = timed(lambda: B.ems_expand(p, merged, tbm, out=(k_exp, v_exp, pos_exp)), K) * 1e3
+    pooled = B.ems_select(p, s_glo, s_loc, want_pooled=True, ws=ws_select)[2]
+    outs2 = B.alloc_evict_merge_outputs(p, "cuda")
+    out["evict_merge_kv_weighted"] = timed(
+        lambda: B.ems_evict_merge_variant(p, B.EMS_SIM_KEY_VALUE, k, v, pooled, imp, tbm, ws=ws_merge,
+                                          out=outs2), K) * 1e3
+    g = p.q_heads // p.kv_heads
+    if g in (1, 2, 4, 8):
+        B.ems_evict_merge(p, k, v, imp, tbm, ws=ws_merge, out=outs2)     # a cache the steps may overwrite
+        state = [B.DecodeState(p, outs2["k_out"], outs2["v_out"])]
+        out["decode_init"] = timed(lambda: B.ems_decode_init(p, outs2, tbm, s_glo, s_loc, state=state[0]), K) * 1e3
+        n = args.decode_steps
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        qn = torch.randn((n, w.batch, w.q_heads, w.head_dim), device="cuda", generator=gen).to(p.torch_dtype)
+        kn = torch.randn((n, w.batch, w.kv_heads, w.head_dim), device="cuda", generator=gen).to(p.torch_dtype)
+        vn = torch.randn((n, w.batch, w.kv_heads, w.head_dim), device="cuda", generator=gen).to(p.torch_dtype)
+        ws = torch.empty(B.ems_decode_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+        res = dict(decision=torch.empty((w.batch, w.kv_heads, 2), dtype=torch.int32, device="cuda"),
+                   sim=torch.empty((w.batch, w.kv_heads), dtype=torch.float32, device="cuda"), attn=None)
+        t = [0]
+
+        def one():
+            B.ems_decode_step(p, state[0], t[0], qn[t[0] % n], kn[t[0] % n], vn[t[0] % n], ws=ws, out=res)
+            t[0] += 1
+        for _ in range(4):
+            one()
+        out["decode_step"] = timed(one, n) * 1e3
+        e = 4 if args.f32 else 2
+        per_head = (w.budget + n_imp) * w.head_dim * e + n_exp * 40
+        out["decode_step_algorithmic_bytes"] = per_head * w.batch * w.kv_heads
+    return {k_: round(v_, 1) for k_, v_ in out.items()}
 
 
 if __name__ == "__main__":

@@ -8,6 +8,9 @@
  *
  *     ems_global_local_score  ->  ems_select  ->  ems_evict_merge
  *
+ * and, for the generation that follows, ems_expand (run-time keys/values of the compact
+ * cache) and ems_decode_init -> ems_decode_step per generated token.
+ *
  * Conventions shared by every entry point
  *   - Every tensor pointer is a DEVICE pointer, contiguous and row-major, owned by the
  *     caller.  The library never allocates, frees or synchronises: work is enqueued on
@@ -217,6 +220,90 @@ int ems_expand(const ems_params* p, const void* k_cache, const void* v_cache,
                const int32_t* kept_pos, const int32_t* tbm_idx, const int32_t* tbm_dest,
                const float* k_norm, void* k_exp, void* v_exp, int32_t* pos_exp,
                void* hip_stream);
+
+/*
+ * Decode-time state of one layer's compressed cache (Sec. 3.2, decoding paragraph; Sec. 5
+ * "Memory analysis": besides the budget-sized cache, one scalar per kept token for s_Glo,
+ * s_Loc^past, s_Loc^cur, the key norm and the position look-up-table).  Every member is a
+ * DEVICE pointer owned by the caller; T = N_imp + N_tbm + window tokens per head: the
+ * look-up-table's N_imp + N_tbm elements (the centres first), then the window ring.
+ *   k_cache, v_cache [B, Hkv, budget + 1, D] `dtype`: rows 0..N_imp-1 the entries, rows
+ *                    N_imp..budget-1 the window ring (k_out / v_out of ems_evict_merge, updated
+ *                    in place)
+ *   row_norm    [B, Hkv, budget] f32  key norm of each row's centre token
+ *   entry_count [B, Hkv, N_imp]  i32  tokens averaged into each entry
+ *   entry_tok   [B, Hkv, N_imp]  i32  table index of each entry's centre token
+ *   tok_pos     [B, Hkv, T] i32  position, -1 = free element
+ *   tok_row     [B, Hkv, T] i32  cache row the token lives in, -1 = free element
+ *   tok_norm, tok_glo, tok_past, tok_cur [B, Hkv, T] f32
+ * A token's run-time key is (tok_norm / row_norm[row]) * k_cache[row], its value v_cache[row].
+ */
+typedef struct {
+    void* k_cache;
+    void* v_cache;
+    float* row_norm;
+    int32_t* entry_count;
+    int32_t* entry_tok;
+    int32_t* tok_pos;
+    int32_t* tok_row;
+    float* tok_norm;
+    float* tok_glo;
+    float* tok_past;
+    float* tok_cur;
+} ems_decode_state;
+
+/* Bytes of device scratch ems_decode_step needs (host only). */
+int ems_decode_workspace_bytes(const ems_params* p, size_t* decode_ws);
+
+/*
+ * Fills the table and the scalars of `state` from what the prefill path returned (Sec. 3.2:
+ * the prefill's s_Glo and s_Loc are stored for the generation; s_Loc is the first
+ * s_Loc^past, s_Loc^cur starts at zero).  state->k_cache / v_cache must already hold
+ * ems_evict_merge's k_out / v_out; they are read (window-row norms), not written.
+ *   s_glo, s_loc in: device [B, Hkv, N] f32 (ems_global_local_score)
+ *   kept_pos, tbm_dest, k_norm, slot_count in: ems_evict_merge's outputs; tbm_idx: ems_select's
+ * To-be-merged tokens that went to the zero class get free table elements.
+ */
+int ems_decode_init(const ems_params* p, const float* s_glo, const float* s_loc,
+                    const int32_t* kept_pos, const int32_t* tbm_idx, const int32_t* tbm_dest,
+                    const float* k_norm, const int32_t* slot_count,
+                    const ems_decode_state* state, void* hip_stream);
+
+/*
+ * One generated token (Sec. 3.2, decoding paragraph; App. A "Evict-then-Merge Details"),
+ * for all heads in one launch.  `step` = number of tokens generated before this one; the new
+ * token's position is seq_len + step.  In order, per kv-head:
+ *   1. attention row of the new queries (q-heads of the group, Eq. 1) over the run-time
+ *      cache -- every live table element expanded, the window tokens, the new token itself;
+ *   2. s_Glo and s_Loc^cur of every live token += the row (summed over the group);
+ *   3. the oldest window token leaves the window; the new token takes its ring slot
+ *      (row N_imp + step % window);
+ *   4. the least important class centre -- Eq. 2 on its centre token's scalars, s_Loc =
+ *      past + cur, alignment factor over all live tokens, lowest slot on ties -- becomes the
+ *      single to-be-merged token;
+ *   5. its destination is the other centre with the highest cosine of the stored entry keys
+ *      (Eq. 5, lowest slot on ties); it merges iff that cosine exceeds tau, else it goes to
+ *      the zero class (eviction);
+ *   6. merge: the destination entry becomes the count-weighted mean of the two entries (values;
+ *      unit-key means rescaled by the destination's centre norm) and the tokens that shared
+ *      the departed entry now point to the destination; evict: their table elements are
+ *      freed.  The token that left the window becomes the centre of the vacated entry and
+ *      takes the departed centre's table element, so budget and table size stay constant;
+ *   7. after every `window` steps s_Loc^past = s_Loc^cur, s_Loc^cur = 0.
+ *   state        in/out
+ *   q_new        in : device [B, Hq, D] `dtype`;  k_new, v_new in: device [B, Hkv, D] `dtype`
+ *   attn_opt     out: device [B, Hq, T + 1] f32 attention weights (free elements 0, last =
+ *                     the new token), or NULL
+ *   decision_opt out: device [B, Hkv, 2] i32 (to-be-merged entry, destination or -1), or NULL
+ *   sim_opt      out: device [B, Hkv] f32 the best cosine, or NULL
+ *   ws           device scratch of at least decode_ws bytes
+ * Supports Hq / Hkv in {1, 2, 4, 8}.  Steps on one state must be enqueued in order on one
+ * stream.
+ */
+int ems_decode_step(const ems_params* p, const ems_decode_state* state, int32_t step,
+                    const void* q_new, const void* k_new, const void* v_new,
+                    float* attn_opt, int32_t* decision_opt, float* sim_opt,
+                    void* ws, size_t ws_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -104,7 +104,9 @@ def global_local(glo, loc):
 def decode_step(st, step, window, budget, tau, softmax_scale, q_new, k_new, v_new, pos_new):
     """One generated token for ONE head group: q_new [G, D]; k_new, v_new [D].  `step` counts
     the generated tokens before this one.  Updates `st` in place and returns what was
-    decided: dict(attn [G, E+W+1], tbm_entry, dest (-1 = zero class), sim)."""
+    decided: dict(attn [G, E+W+1], tbm_entry, dest (-1 = zero class), sim, and for diagnosis
+    centre_score [n_imp] (Eq. 2 of every centre) and centre_sims [n_imp] (cosines to the
+    to-be-merged entry))."""
     W, n_imp = window, budget - window
     T = len(st["tok_row"])
     E = T - W
@@ -196,4 +198,4 @@ def decode_step(st, step, window, budget, tau, softmax_scale, q_new, k_new, v_ne
     if (step + 1) % W == 0:
         st["tok_past"] = st["tok_cur"].copy()
         st["tok_cur"] = np.zeros(T)
-    return dict(attn=attn, tbm_entry=s_star, dest=d, sim=sim)
+    return dict(attn=attn, tbm_entry=s_star, dest=d, sim=sim, centre_score=score, centre_sims=sims)

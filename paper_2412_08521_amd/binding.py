@@ -28,7 +28,8 @@ EMS_SIM_KEY_VALUE = 2
 
 EXPORTS = ("ems_version", "ems_strerror", "ems_partition_sizes", "ems_workspace_bytes",
            "ems_global_local_score", "ems_attention_lse", "ems_global_local_score_from_lse",
-           "ems_select", "ems_evict_merge", "ems_evict_merge_variant", "ems_expand")
+           "ems_select", "ems_evict_merge", "ems_evict_merge_variant", "ems_expand",
+           "ems_decode_workspace_bytes", "ems_decode_init", "ems_decode_step")
 
 
 class ems_params(C.Structure):
@@ -36,6 +37,14 @@ class ems_params(C.Structure):
                 ("head_dim", C.c_int32), ("seq_len", C.c_int32), ("window", C.c_int32),
                 ("budget", C.c_int32), ("merge_ratio", C.c_float), ("tau", C.c_float),
                 ("pool_kernel", C.c_int32), ("softmax_scale", C.c_float), ("dtype", C.c_int32)]
+
+
+STATE_FIELDS = ("k_cache", "v_cache", "row_norm", "entry_count", "entry_tok", "tok_pos", "tok_row",
+                "tok_norm", "tok_glo", "tok_past", "tok_cur")
+
+
+class ems_decode_state(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in STATE_FIELDS]
 
 
 class EmsError(RuntimeError):
@@ -92,6 +101,10 @@ def lib():
         l.ems_evict_merge.argtypes = [P] + [C.c_void_p] * 12 + [C.c_size_t, C.c_void_p]
         l.ems_evict_merge_variant.argtypes = ([P, C.c_int] + [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p])
         l.ems_expand.argtypes = [P] + [C.c_void_p] * 10
+        S = C.POINTER(ems_decode_state)
+        l.ems_decode_workspace_bytes.argtypes = [P, C.POINTER(C.c_size_t)]
+        l.ems_decode_init.argtypes = [P] + [C.c_void_p] * 7 + [S, C.c_void_p]
+        l.ems_decode_step.argtypes = [P, S, C.c_int32] + [C.c_void_p] * 6 + [C.c_void_p, C.c_size_t, C.c_void_p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = C.c_int
         _lib = l
@@ -319,3 +332,84 @@ def ems_expand(p: EmsParams, merged: dict, tbm_idx, out=None):
     if rc != EMS_OK:
         raise EmsError(rc, "ems_expand")
     return k_exp, v_exp, pos
+
+
+def ems_decode_workspace_bytes(p: EmsParams) -> int:
+    n = C.c_size_t(0)
+    cp = p.c()
+    rc = lib().ems_decode_workspace_bytes(C.byref(cp), C.byref(n))
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_decode_workspace_bytes")
+    return int(n.value)
+
+
+class DecodeState:
+    """Device tensors of the decode-time state (see ems_decode_state in include/ems.h)."""
+
+    def __init__(self, p: EmsParams, k_cache, v_cache):
+        n_imp, n_tbm = ems_partition_sizes(p)
+        B, H, Nb = p.batch, p.kv_heads, p.budget
+        T = n_imp + n_tbm + p.window
+        dev = k_cache.device
+        _check_tensor(k_cache, (B, H, Nb + 1, p.head_dim), p.torch_dtype, "k_cache")
+        _check_tensor(v_cache, (B, H, Nb + 1, p.head_dim), p.torch_dtype, "v_cache")
+        i32, f32 = torch.int32, torch.float32
+        self.n_tokens = T
+        self.k_cache, self.v_cache = k_cache, v_cache
+        self.row_norm = torch.zeros((B, H, Nb), dtype=f32, device=dev)
+        self.entry_count = torch.zeros((B, H, n_imp), dtype=i32, device=dev)
+        self.entry_tok = torch.zeros((B, H, n_imp), dtype=i32, device=dev)
+        self.tok_pos = torch.full((B, H, T), -1, dtype=i32, device=dev)
+        self.tok_row = torch.full((B, H, T), -1, dtype=i32, device=dev)
+        self.tok_norm = torch.zeros((B, H, T), dtype=f32, device=dev)
+        self.tok_glo = torch.zeros((B, H, T), dtype=f32, device=dev)
+        self.tok_past = torch.zeros((B, H, T), dtype=f32, device=dev)
+        self.tok_cur = torch.zeros((B, H, T), dtype=f32, device=dev)
+
+    def c(self) -> ems_decode_state:
+        return ems_decode_state(*[getattr(self, name).data_ptr() for name in STATE_FIELDS])
+
+
+def ems_decode_init(p: EmsParams, merged: dict, tbm_idx, s_glo, s_loc, state=None) -> DecodeState:
+    """State for the generation from ems_evict_merge's outputs (`merged`; its k_out / v_out
+    become the live cache and are updated in place by ems_decode_step)."""
+    n_imp, n_tbm = ems_partition_sizes(p)
+    shape = (p.batch, p.kv_heads, p.seq_len)
+    _check_tensor(s_glo, shape, torch.float32, "s_glo")
+    _check_tensor(s_loc, shape, torch.float32, "s_loc")
+    _check_tensor(merged["kept_pos"], (p.batch, p.kv_heads, p.budget), torch.int32, "kept_pos")
+    _check_tensor(merged["k_norm"], (p.batch, p.kv_heads, n_imp + n_tbm), torch.float32, "k_norm")
+    _check_tensor(merged["tbm_dest"], (p.batch, p.kv_heads, n_tbm), torch.int32, "tbm_dest")
+    _check_tensor(merged["slot_count"], (p.batch, p.kv_heads, n_imp + 1), torch.int32, "slot_count")
+    _check_tensor(tbm_idx, (p.batch, p.kv_heads, n_tbm), torch.int32, "tbm_idx")
+    st = state if state is not None else DecodeState(p, merged["k_out"], merged["v_out"])
+    has = n_tbm > 0
+    cp, cs = p.c(), st.c()
+    rc = lib().ems_decode_init(C.byref(cp), _ptr(s_glo), _ptr(s_loc), _ptr(merged["kept_pos"]),
+                               _ptr(tbm_idx) if has else None, _ptr(merged["tbm_dest"]) if has else None,
+                               _ptr(merged["k_norm"]), _ptr(merged["slot_count"]), C.byref(cs), _stream())
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_decode_init")
+    return st
+
+
+def ems_decode_step(p: EmsParams, st: DecodeState, step: int, q_new, k_new, v_new, want_attn=False,
+                    ws=None, out=None):
+    """One generated token -> dict(decision [B,Hkv,2], sim [B,Hkv], attn [B,Hq,T+1] or None)."""
+    _check_tensor(q_new, (p.batch, p.q_heads, p.head_dim), p.torch_dtype, "q_new")
+    _check_tensor(k_new, (p.batch, p.kv_heads, p.head_dim), p.torch_dtype, "k_new")
+    _check_tensor(v_new, (p.batch, p.kv_heads, p.head_dim), p.torch_dtype, "v_new")
+    dev = q_new.device
+    ws = _workspace(ems_decode_workspace_bytes(p), dev, ws)
+    if out is None:
+        out = dict(decision=torch.empty((p.batch, p.kv_heads, 2), dtype=torch.int32, device=dev),
+                   sim=torch.empty((p.batch, p.kv_heads), dtype=torch.float32, device=dev),
+                   attn=torch.empty((p.batch, p.q_heads, st.n_tokens + 1), dtype=torch.float32, device=dev)
+                   if want_attn else None)
+    cp, cs = p.c(), st.c()
+    rc = lib().ems_decode_step(C.byref(cp), C.byref(cs), int(step), _ptr(q_new), _ptr(k_new), _ptr(v_new),
+                               _ptr(out.get("attn")), _ptr(out["decision"]), _ptr(out["sim"]),
+                               _ptr(ws), ws.numel(), _stream())
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_decode_step")
+    return out

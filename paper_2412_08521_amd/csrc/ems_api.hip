@@ -296,4 +296,94 @@ int ems_expand(const ems_params* p, const void* k_cache, const void* v_cache,
     return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
 }
 
+static bool decode_params_ok(const ems_params* p, int* why)
+{
+    if (!full_params_ok(p, why)) return false;
+    const int g = p->q_heads / p->kv_heads;
+    *why = EMS_ERR_UNSUPPORTED;
+    return g == 1 || g == 2 || g == 4 || g == 8;
+}
+
+static size_t decode_ws_bytes(const ems_params* p)
+{
+    const size_t bkv = (size_t)p->batch * p->kv_heads;
+    const size_t g = (size_t)(p->q_heads / p->kv_heads);
+    return align_up(sizeof(float) * bkv * g * (size_t)p->budget) +
+           align_up(sizeof(float) * bkv * (size_t)(p->budget - p->window));
+}
+
+static bool state_ok(const ems_decode_state* s)
+{
+    return s && s->k_cache && s->v_cache && s->row_norm && s->entry_count && s->entry_tok && s->tok_pos &&
+           s->tok_row && s->tok_norm && s->tok_glo && s->tok_past && s->tok_cur;
+}
+
+static ems::DecodeState to_internal(const ems_decode_state* s)
+{
+    ems::DecodeState d{};
+    d.k_cache = s->k_cache; d.v_cache = s->v_cache; d.row_norm = s->row_norm;
+    d.entry_count = s->entry_count; d.entry_tok = s->entry_tok; d.tok_pos = s->tok_pos;
+    d.tok_row = s->tok_row; d.tok_norm = s->tok_norm; d.tok_glo = s->tok_glo;
+    d.tok_past = s->tok_past; d.tok_cur = s->tok_cur;
+    return d;
+}
+
+int ems_decode_workspace_bytes(const ems_params* p, size_t* decode_ws)
+{
+    int why;
+    if (!decode_params_ok(p, &why)) return why;
+    if (decode_ws) *decode_ws = decode_ws_bytes(p);
+    return EMS_OK;
+}
+
+int ems_decode_init(const ems_params* p, const float* s_glo, const float* s_loc,
+                    const int32_t* kept_pos, const int32_t* tbm_idx, const int32_t* tbm_dest,
+                    const float* k_norm, const int32_t* slot_count,
+                    const ems_decode_state* state, void* hip_stream)
+{
+    int why;
+    if (!decode_params_ok(p, &why)) return why;
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+    if (!s_glo || !s_loc || !kept_pos || !k_norm || !slot_count || !state_ok(state)) return EMS_ERR_INVALID_ARG;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest)) return EMS_ERR_INVALID_ARG;
+    ems::DecodeInitArgs a{};
+    a.st = to_internal(state);
+    a.s_glo = s_glo; a.s_loc = s_loc; a.kept_pos = kept_pos; a.tbm_idx = tbm_idx; a.tbm_dest = tbm_dest;
+    a.k_norm = k_norm; a.slot_count = slot_count;
+    a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len;
+    a.window = p->window; a.budget = p->budget; a.n_imp = n_imp; a.n_tbm = n_tbm;
+    const hipError_t e = ems::launch_decode_init(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
+int ems_decode_step(const ems_params* p, const ems_decode_state* state, int32_t step,
+                    const void* q_new, const void* k_new, const void* v_new,
+                    float* attn_opt, int32_t* decision_opt, float* sim_opt,
+                    void* ws, size_t ws_bytes, void* hip_stream)
+{
+    int why;
+    if (!decode_params_ok(p, &why)) return why;
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+    if (!state_ok(state) || !q_new || !k_new || !v_new) return EMS_ERR_INVALID_ARG;
+    if (step < 0 || (long long)p->seq_len + step > 0x7fffffffll) return EMS_ERR_INVALID_ARG;
+    if (!ws_ok(ws, ws_bytes, decode_ws_bytes(p))) return EMS_ERR_WORKSPACE;
+    const size_t bkv = (size_t)p->batch * p->kv_heads;
+    const int g = p->q_heads / p->kv_heads;
+    ems::DecodeStepArgs a{};
+    a.st = to_internal(state);
+    a.q_new = q_new; a.k_new = k_new; a.v_new = v_new;
+    a.attn_opt = attn_opt; a.decision_opt = decision_opt; a.sim_opt = sim_opt;
+    a.ws_dot = static_cast<float*>(ws);
+    a.ws_en = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up(sizeof(float) * bkv * g * (size_t)p->budget));
+    a.bkv = (int)bkv; a.group = g; a.head_dim = p->head_dim; a.window = p->window; a.budget = p->budget;
+    a.n_imp = n_imp; a.n_tbm = n_tbm; a.step = step; a.pos_new = p->seq_len + step;
+    a.tau = p->tau;
+    const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
+    a.scale_log2e = (float)(scale * 1.4426950408889634074);
+    const hipError_t e = ems::launch_decode_step(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -66,7 +66,50 @@ struct ExpandArgs {
     int bkv, head_dim, window, budget, n_imp, n_tbm;
 };
 
+// Decode-time state of the compressed cache: one row per (batch, kv-head) in every array.
+struct DecodeState {
+    void* k_cache;          // [bkv, budget + 1, D]
+    void* v_cache;
+    float* row_norm;        // [bkv, budget]
+    int32_t* entry_count;   // [bkv, n_imp]
+    int32_t* entry_tok;     // [bkv, n_imp]
+    int32_t* tok_pos;       // [bkv, T]   T = n_imp + n_tbm + window
+    int32_t* tok_row;       // [bkv, T]   cache row, -1 = free element
+    float* tok_norm;
+    float* tok_glo;
+    float* tok_past;
+    float* tok_cur;
+};
+
+struct DecodeInitArgs {
+    DecodeState st;
+    const float* s_glo;     // [bkv, seq_len]
+    const float* s_loc;
+    const int32_t* kept_pos;
+    const int32_t* tbm_idx;
+    const int32_t* tbm_dest;
+    const float* k_norm;
+    const int32_t* slot_count;
+    int bkv, head_dim, seq_len, window, budget, n_imp, n_tbm;
+};
+
+struct DecodeStepArgs {
+    DecodeState st;
+    const void* q_new;      // [bkv * group, D]
+    const void* k_new;      // [bkv, D]
+    const void* v_new;
+    float* attn_opt;        // [bkv * group, T + 1] or null
+    int32_t* decision_opt;  // [bkv, 2] or null
+    float* sim_opt;         // [bkv] or null
+    float* ws_dot;          // [bkv, group, budget]
+    float* ws_en;           // [bkv, n_imp]
+    int bkv, group, head_dim, window, budget, n_imp, n_tbm, step, pos_new;
+    float tau, scale_log2e;
+};
+
 int score_keys_per_block(int dtype_is_f32);
+hipError_t launch_decode_init(const DecodeInitArgs& a, bool f32, hipStream_t st);
+hipError_t launch_decode_step(const DecodeStepArgs& a, bool f32, hipStream_t st);
 hipError_t launch_expand(const ExpandArgs& a, bool f32, hipStream_t st);
 hipError_t launch_score_pass1(const ScoreArgs& a, bool f32, hipStream_t st);   // rows' log-sum-exp
 hipError_t launch_score_pass2(const ScoreArgs& a, bool f32, hipStream_t st);   // column sums

@@ -11,6 +11,7 @@
 //               writer, so there are no atomics and results are reproducible bit for bit.
 #include "ems_common.h"
 #include "ems_kernels.h"
+#include "ems_rows.h"
 
 namespace ems {
 
@@ -21,27 +22,6 @@ template <typename T> struct DestCfg { static constexpr int kStageRows = 64; };
 template <> struct DestCfg<float> { static constexpr int kStageRows = 32; };
 
 __device__ __forceinline__ int clamp_pos(int p, int n) { return min(max(p, 0), n - 1); }
-
-// sum of squares of the 16-byte fragment's elements, in f32
-template <typename T> __device__ __forceinline__ float frag_sumsq(const frag_t& f);
-template <> __device__ __forceinline__ float frag_sumsq<bf16_t>(const frag_t& f)
-{
-    const bf16x8_t v = __builtin_bit_cast(bf16x8_t, f);
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { const float x = (float)v[i]; s = __builtin_fmaf(x, x, s); }
-    return s;
-}
-template <> __device__ __forceinline__ float frag_sumsq<float>(const frag_t& f)
-{
-    const f32x4_t v = __builtin_bit_cast(f32x4_t, f);
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) s = __builtin_fmaf(v[i], v[i], s);
-    return s;
-}
-
-__device__ __forceinline__ float inv_norm(float sumsq) { return sumsq > 0.f ? 1.0f / sqrtf(sumsq) : 0.f; }
 
 // ------------------------------------------------------------------------------------
 // Destination of every TBM token (Eq. 5, then the threshold).  The redundancy is the key
@@ -173,40 +153,6 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
 // has kGroups = 64 / kLpr rows in flight per load; members of a slot are dealt to the
 // groups in ascending order and the groups are added by a fixed butterfly at the end.
 // ------------------------------------------------------------------------------------
-template <typename T> struct Pack;
-template <> struct Pack<bf16_t> {
-    static constexpr int kElems = 8;
-    static __device__ __forceinline__ void unpack(const frag_t& f, float (&x)[8])
-    {
-        const bf16x8_t v = __builtin_bit_cast(bf16x8_t, f);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = (float)v[i];
-    }
-    static __device__ __forceinline__ frag_t pack(const float (&x)[8])
-    {
-        bf16x8_t v;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = (bf16_t)x[i];      // round to nearest even
-        return __builtin_bit_cast(frag_t, v);
-    }
-};
-template <> struct Pack<float> {
-    static constexpr int kElems = 4;
-    static __device__ __forceinline__ void unpack(const frag_t& f, float (&x)[4])
-    {
-        const f32x4_t v = __builtin_bit_cast(f32x4_t, f);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = v[i];
-    }
-    static __device__ __forceinline__ frag_t pack(const float (&x)[4])
-    {
-        f32x4_t v;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = x[i];
-        return __builtin_bit_cast(frag_t, v);
-    }
-};
-
 template <typename T, int D>
 struct RowAcc {
     static constexpr int kE = Pack<T>::kElems;

@@ -112,3 +112,27 @@ def test_null_pointers_and_workspace_errors(lib):
     assert lib.ems_evict_merge_variant(C.byref(cp), 2, *args) == B.EMS_ERR_INVALID_ARG
     bad = _bad(budget=16).c()
     assert lib.ems_expand(C.byref(bad), d, d, d, d, d, d, d, d, d, None) == B.EMS_ERR_INVALID_ARG
+
+
+def test_decode_argument_errors(lib):
+    p = _bad()
+    cp = p.c()
+    d = C.c_void_p(256)
+    st = B.ems_decode_state(*[256] * len(B.STATE_FIELDS))
+    assert C.sizeof(B.ems_decode_state) == 11 * C.sizeof(C.c_void_p)
+    need = B.ems_decode_workspace_bytes(p)
+    assert need >= 4 * (2 * 2 * 64 + 2 * 48) and need % 256 == 0
+    # null state member, null token, negative step, workspace too small
+    hole = B.ems_decode_state(*([256] * 5 + [0] + [256] * 5))
+    assert lib.ems_decode_step(C.byref(cp), C.byref(hole), 0, d, d, d, None, None, None, d, need, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_decode_step(C.byref(cp), C.byref(st), 0, None, d, d, None, None, None, d, need, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_decode_step(C.byref(cp), C.byref(st), -1, d, d, d, None, None, None, d, need, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_decode_step(C.byref(cp), C.byref(st), 0, d, d, d, None, None, None, d, need - 1, None) == B.EMS_ERR_WORKSPACE
+    assert lib.ems_decode_step(C.byref(cp), C.byref(st), 0, d, d, d, None, None, None, C.c_void_p(8), need, None) == B.EMS_ERR_WORKSPACE
+    assert lib.ems_decode_init(C.byref(cp), d, d, d, d, d, d, d, None, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_decode_init(C.byref(cp), None, d, d, d, d, d, d, C.byref(st), None) == B.EMS_ERR_INVALID_ARG
+    # group sizes other than 1, 2, 4, 8 are not built
+    odd = _bad(q_heads=6).c()
+    assert lib.ems_decode_step(C.byref(odd), C.byref(st), 0, d, d, d, None, None, None, d, 1 << 30, None) == B.EMS_ERR_UNSUPPORTED
+    n = C.c_size_t(0)
+    assert lib.ems_decode_workspace_bytes(C.byref(odd), C.byref(n)) == B.EMS_ERR_UNSUPPORTED
