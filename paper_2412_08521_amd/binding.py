@@ -367,7 +367,9 @@ class DecodeState:
         self.tok_cur = torch.zeros((B, H, T), dtype=f32, device=dev)
 
     def c(self) -> ems_decode_state:
-        return ems_decode_state(*[getattr(self, name).data_ptr() for name in STATE_FIELDS])
+        if getattr(self, "_c", None) is None:                # the tensors never move
+            self._c = ems_decode_state(*[getattr(self, name).data_ptr() for name in STATE_FIELDS])
+        return self._c
 
 
 def ems_decode_init(p: EmsParams, merged: dict, tbm_idx, s_glo, s_loc, state=None) -> DecodeState:
@@ -400,7 +402,8 @@ def ems_decode_step(p: EmsParams, st: DecodeState, step: int, q_new, k_new, v_ne
     _check_tensor(k_new, (p.batch, p.kv_heads, p.head_dim), p.torch_dtype, "k_new")
     _check_tensor(v_new, (p.batch, p.kv_heads, p.head_dim), p.torch_dtype, "v_new")
     dev = q_new.device
-    ws = _workspace(ems_decode_workspace_bytes(p), dev, ws)
+    if ws is None:
+        ws = _workspace(ems_decode_workspace_bytes(p), dev)
     if out is None:
         out = dict(decision=torch.empty((p.batch, p.kv_heads, 2), dtype=torch.int32, device=dev),
                    sim=torch.empty((p.batch, p.kv_heads), dtype=torch.float32, device=dev),

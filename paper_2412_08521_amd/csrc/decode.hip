@@ -131,7 +131,19 @@ __global__ __launch_bounds__(256) void decode_init_kernel(DecodeInitArgs a)
     a.st.tok_cur[o] = 0.f;
 }
 
+// (max, sum of 2^(x - max)) pairs of an online softmax; combine is associative
+__device__ __forceinline__ void lse_combine(float& m, float& s, float om, float os)
+{
+    const float M = fmaxf(m, om);
+    const float a = m > -INFINITY ? s * exp2_fast(m - M) : 0.f;
+    const float b = om > -INFINITY ? os * exp2_fast(om - M) : 0.f;
+    m = M;
+    s = a + b;
+}
+
 // ------------------------------------------------------------------------------------
+// Dynamic LDS (floats): dot[G][budget] | rn[budget] | en[n_imp] when that fits, else the
+// same arrays live in the caller's workspace (a.lds_floats == 0).
 template <typename T, int D, int G>
 __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a)
 {
@@ -140,8 +152,10 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
     constexpr int kLpr = Tile<T, D>::kChunksPerRow;          // lanes per cache row
     constexpr int kGroups = kDecBlock / kLpr;                // rows in flight per block
 
+    extern __shared__ float dyn_lds[];
     __shared__ float fbuf[kDecWaves];
     __shared__ int ibuf[kDecWaves];
+    __shared__ float vbuf[2 * G][kDecWaves];                 // vector reductions
     __shared__ float sh_self[G];                             // new query . new key (log2 units)
     __shared__ frag_t old_k[kLpr], old_v[kLpr];              // the token that leaves the window
     __shared__ float old_sc[4];                              // its norm, glo, past, cur
@@ -152,6 +166,7 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
     const int Tn = E + W;
     const int bkv = blockIdx.x;
     const int tid = threadIdx.x;
+    const int lane = tid % kWave, wave = tid / kWave;
     const int grp = tid / kLpr, piece = tid % kLpr;
 
     char* Kc = reinterpret_cast<char*>(a.st.k_cache) + (size_t)bkv * (Nb + 1) * D * sizeof(T);
@@ -165,19 +180,24 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
     float* tok_glo = a.st.tok_glo + (size_t)bkv * Tn;
     float* tok_past = a.st.tok_past + (size_t)bkv * Tn;
     float* tok_cur = a.st.tok_cur + (size_t)bkv * Tn;
-    float* dot = a.ws_dot + (size_t)bkv * G * Nb;            // [G][budget] q_g . cache row
-    float* en = a.ws_en + (size_t)bkv * n_imp;               // norm of every stored entry key
+    const bool in_lds = a.lds_floats > 0;                    // block-uniform
+    float* stage = in_lds ? dyn_lds : a.ws + (size_t)bkv * ((size_t)(G + 1) * Nb + n_imp);
+    float* dot = stage;                                      // [G][budget] q_g . cache row
+    float* rn_of = stage + (size_t)G * Nb;                   // [budget] copy of row_norm
+    float* en = rn_of + Nb;                                  // [n_imp] norm of every stored entry key
     const char* qn = reinterpret_cast<const char*>(a.q_new) + (size_t)bkv * G * D * sizeof(T);
     const char* kn = reinterpret_cast<const char*>(a.k_new) + (size_t)bkv * D * sizeof(T);
     const char* vn = reinterpret_cast<const char*>(a.v_new) + (size_t)bkv * D * sizeof(T);
 
     // ---- phase 1: one dot product per cache row and q-head, the rows' own norms -------
+    const int ct_mine = tid < n_imp ? entry_tok[tid] : 0;    // early: used in phase 4
     float qf[G][kE];
 #pragma unroll
     for (int g = 0; g < G; ++g)
         P::unpack(*reinterpret_cast<const frag_t*>(qn + ((size_t)g * kLpr + piece) * 16), qf[g]);
     const frag_t new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
     const frag_t new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
+    for (int r = tid; r < Nb; r += kDecBlock) rn_of[r] = row_norm[r];
 
     for (int r = grp; r < Nb + 1; r += kGroups) {
         // iteration r == Nb stands for the new token's own key
@@ -215,45 +235,54 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
     __syncthreads();
 
     // ---- phase 2: softmax over the live tokens and the new token (Eq. 1) ---------------
-    // logit of token j in row r: scale * (|k_j| / |centre of r|) * (q . row r)
-    float m[G];
+    // logit of token j in row r: scale * (|k_j| / |centre of r|) * (q . row r); one sweep
+    // keeps a running (max, sum) per q-head, a second sweep forms the weights
+    float m[G], sum[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) m[g] = sh_self[g];
+    for (int g = 0; g < G; ++g) { m[g] = tid == 0 ? sh_self[g] : -INFINITY; sum[g] = tid == 0 ? 1.f : 0.f; }
     for (int j = tid; j < Tn; j += kDecBlock) {
         const int r = tok_row[j];
         if (r < 0) continue;
-        const float rn = row_norm[r];
+        const float rn = rn_of[r];
         const float c = a.scale_log2e * (rn > 0.f ? tok_norm[j] / rn : 0.f);
 #pragma unroll
-        for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], c * dot[(size_t)g * Nb + r]);
+        for (int g = 0; g < G; ++g) lse_combine(m[g], sum[g], c * dot[(size_t)g * Nb + r], 1.f);
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) m[g] = block_max(m[g], fbuf);
-    float sum[G];
+    for (int o = 32; o >= 1; o >>= 1) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) sum[g] = tid == 0 ? exp2_fast(sh_self[g] - m[g]) : 0.f;
-    for (int j = tid; j < Tn; j += kDecBlock) {
-        const int r = tok_row[j];
-        if (r < 0) continue;
-        const float rn = row_norm[r];
-        const float c = a.scale_log2e * (rn > 0.f ? tok_norm[j] / rn : 0.f);
-#pragma unroll
-        for (int g = 0; g < G; ++g) sum[g] += exp2_fast(c * dot[(size_t)g * Nb + r] - m[g]);
+        for (int g = 0; g < G; ++g) lse_combine(m[g], sum[g], __shfl_xor(m[g], o), __shfl_xor(sum[g], o));
     }
+    if (lane == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) sum[g] = 1.0f / block_add(sum[g], fbuf);
-    // accumulate the row into s_Glo and s_Loc^cur (Sec. 3.2)
+        for (int g = 0; g < G; ++g) { vbuf[2 * g][wave] = m[g]; vbuf[2 * g + 1][wave] = sum[g]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = vbuf[2 * g][lane % kDecWaves];
+        sum[g] = vbuf[2 * g + 1][lane % kDecWaves];
+#pragma unroll
+        for (int o = kDecWaves / 2; o >= 1; o >>= 1) lse_combine(m[g], sum[g], __shfl_xor(m[g], o), __shfl_xor(sum[g], o));
+        sum[g] = 1.0f / sum[g];
+    }
+    // accumulate the row into s_Glo and s_Loc^cur (Sec. 3.2); the sums that Eq. 2 needs
+    // (phase 4) are those of the updated scalars
+    float sg = 0.f, sl = 0.f;
     for (int j = tid; j < Tn; j += kDecBlock) {
         const int r = tok_row[j];
         float w[G];
-        float tot = 0.f;
         if (r >= 0) {
-            const float rn = row_norm[r];
+            const float rn = rn_of[r];
             const float c = a.scale_log2e * (rn > 0.f ? tok_norm[j] / rn : 0.f);
+            float tot = 0.f;
 #pragma unroll
             for (int g = 0; g < G; ++g) { w[g] = exp2_fast(c * dot[(size_t)g * Nb + r] - m[g]) * sum[g]; tot += w[g]; }
-            tok_glo[j] += tot;
-            tok_cur[j] += tot;
+            const float glo = tok_glo[j] + tot, cur = tok_cur[j] + tot;
+            tok_glo[j] = glo;
+            tok_cur[j] = cur;
+            sg += glo;
+            sl += tok_past[j] + cur;
         } else {
 #pragma unroll
             for (int g = 0; g < G; ++g) w[g] = 0.f;
@@ -270,7 +299,11 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
         self_tot += w;
         if (a.attn_opt && tid == 0) a.attn_opt[((size_t)bkv * G + g) * (Tn + 1) + Tn] = w;
     }
-    __syncthreads();
+    if (tid == 0) { sg += self_tot; sl += self_tot; }        // the new token: glo = cur = its own weight
+    sg = wave_add(sg);
+    sl = wave_add(sl);
+    __syncthreads();                                         // vbuf free; every token's scalars written
+    if (lane == 0) { vbuf[0][wave] = sg; vbuf[1][wave] = sl; }
 
     // ---- phase 3: the oldest window token leaves, the new token takes its ring slot ----
     const int ring = a.step % W;
@@ -291,20 +324,14 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
     __syncthreads();
 
     // ---- phase 4: least important class centre (Eq. 2 on the tokens' scalars) ----------
-    float sg = 0.f, sl = 0.f;
-    for (int j = tid; j < Tn; j += kDecBlock) {
-        if (tok_row[j] < 0) continue;
-        sg += tok_glo[j];
-        sl += tok_past[j] + tok_cur[j];
-    }
-    if (tid == 0) { sg += old_sc[1]; sl += old_sc[2] + old_sc[3]; }
-    sg = block_add(sg, fbuf);
-    sl = block_add(sl, fbuf);
+    sg = 0.f; sl = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) { sg += vbuf[0][w]; sl += vbuf[1][w]; }      // fixed order
     const float align = sg > 0.f ? sl / sg : 0.f;
     float bv = 0.f;
     int bi = -1;
     for (int s = tid; s < n_imp; s += kDecBlock) {
-        const int ct = entry_tok[s];
+        const int ct = s == tid ? ct_mine : entry_tok[s];
         const float sc = fmaxf(tok_glo[ct] * align, tok_past[ct] + tok_cur[ct]);
         if (better<true>(sc, s, bv, bi)) { bv = sc; bi = s; }
     }
@@ -405,11 +432,12 @@ template <typename T, int D>
 static hipError_t launch_decode_step_t(const DecodeStepArgs& a, hipStream_t st)
 {
     const dim3 g(a.bkv), b(kDecBlock);
+    const size_t lds = sizeof(float) * (size_t)a.lds_floats;
     switch (a.group) {
-        case 1: hipLaunchKernelGGL((decode_step_kernel<T, D, 1>), g, b, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((decode_step_kernel<T, D, 2>), g, b, 0, st, a); break;
-        case 4: hipLaunchKernelGGL((decode_step_kernel<T, D, 4>), g, b, 0, st, a); break;
-        case 8: hipLaunchKernelGGL((decode_step_kernel<T, D, 8>), g, b, 0, st, a); break;
+        case 1: hipLaunchKernelGGL((decode_step_kernel<T, D, 1>), g, b, lds, st, a); break;
+        case 2: hipLaunchKernelGGL((decode_step_kernel<T, D, 2>), g, b, lds, st, a); break;
+        case 4: hipLaunchKernelGGL((decode_step_kernel<T, D, 4>), g, b, lds, st, a); break;
+        case 8: hipLaunchKernelGGL((decode_step_kernel<T, D, 8>), g, b, lds, st, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

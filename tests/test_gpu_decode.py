@@ -83,14 +83,21 @@ def test_decode_init_matches_oracle(shape, mode):
     assert (st.tok_row < 0).any() and (st.tok_row >= 0).any()
 
 
+# a budget whose per-row staging does not fit in LDS: the kernel stages in the workspace instead
+BIG = (1, 8, 1, 64, 4000, 8, 1600, 0.5)
+
+
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("tau", [0.3, -2.0, 2.0])
-@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("shape", SHAPES + [BIG])
 def test_decode_steps_match_oracle(shape, tau, mode):
+    if shape == BIG and (tau != 0.3 or mode != B.EMS_BF16):
+        pytest.skip("the large-budget case runs once")
     _log("decode_step", shape, "tau", tau, "mode", mode)
     p, merged, tbm, s_glo, s_loc, st = _prefill(shape, mode, tau, seed=shape[6])
     n_imp, n_tbm = B.ems_partition_sizes(p)
     G, W, D = p.q_heads // p.kv_heads, p.window, p.head_dim
+    assert (shape == BIG) == (4 * ((G + 1) * p.budget + n_imp) > 60 * 1024)
     rng = np.random.default_rng(17)
     # merged rows: one bf16 rounding of the stored row; in f32 mode about ten float32 roundings with
     # cancellation between the two entries (the f32 bar of the prefill merge is the same 1e-5)
@@ -145,7 +152,7 @@ def test_decode_steps_match_oracle(shape, tau, mode):
         assert n_merge == 0
     elif tau <= -1:
         assert n_evict == 0
-    else:
+    elif shape != BIG:                                    # with 1592 random centres something is always similar
         assert n_merge > 0 and n_evict > 0, (n_merge, n_evict)
 
 
