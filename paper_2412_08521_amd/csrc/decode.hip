@@ -16,45 +16,36 @@
 
 namespace ems {
 
-constexpr int kDecBlock = 1024;
-constexpr int kDecWaves = kDecBlock / kWave;
-
-// ---- block-wide reductions; `buf` has kDecWaves slots per value; every thread must call
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
-}
-__device__ __forceinline__ float wave_add(float v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-__device__ __forceinline__ float block_max(float v, float* buf)
+// ---- block-wide reductions over kWaves waves.  Every thread of the block must call; the
+// result is identical in every thread (the combines are commutative, so the butterflies
+// give every lane the same value).
+template <int kWaves, int kN, bool kMax>
+__device__ __forceinline__ void block_reduce(float (&v)[kN], float (*buf)[kWaves])
 {
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    v = wave_max(v);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+#pragma unroll
+        for (int i = 0; i < kN; ++i) {
+            const float x = __shfl_xor(v[i], o);
+            v[i] = kMax ? fmaxf(v[i], x) : v[i] + x;
+        }
+    }
     __syncthreads();                                    // buf free again
-    if (lane == 0) buf[wave] = v;
-    __syncthreads();
-    float r = buf[0];
+    if (lane == 0) {
 #pragma unroll
-    for (int w = 1; w < kDecWaves; ++w) r = fmaxf(r, buf[w]);
-    return r;
-}
-__device__ __forceinline__ float block_add(float v, float* buf)
-{
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    v = wave_add(v);
+        for (int i = 0; i < kN; ++i) buf[i][wave] = v[i];
+    }
     __syncthreads();
-    if (lane == 0) buf[wave] = v;
-    __syncthreads();
-    float r = 0.f;
 #pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) r += buf[w];    // fixed order
-    return r;
+    for (int i = 0; i < kN; ++i) {
+        v[i] = buf[i][lane % kWaves];
+#pragma unroll
+        for (int o = kWaves / 2; o >= 1; o >>= 1) {
+            const float x = __shfl_xor(v[i], o);
+            v[i] = kMax ? fmaxf(v[i], x) : v[i] + x;
+        }
+    }
 }
 // arg-min (kMin) or arg-max of (value, index) pairs, lowest index on ties; index < 0 = none
 template <bool kMin>
@@ -65,7 +56,7 @@ __device__ __forceinline__ bool better(float v, int i, float bv, int bi)
     if (kMin ? v < bv : v > bv) return true;
     return v == bv && i < bi;
 }
-template <bool kMin>
+template <int kWaves, bool kMin>
 __device__ __forceinline__ void block_arg(float& v, int& i, float* fbuf, int* ibuf)
 {
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -78,10 +69,22 @@ __device__ __forceinline__ void block_arg(float& v, int& i, float* fbuf, int* ib
     __syncthreads();
     if (lane == 0) { fbuf[wave] = v; ibuf[wave] = i; }
     __syncthreads();
-    v = fbuf[0]; i = ibuf[0];
+    v = fbuf[lane % kWaves]; i = ibuf[lane % kWaves];
 #pragma unroll
-    for (int w = 1; w < kDecWaves; ++w)
-        if (better<kMin>(fbuf[w], ibuf[w], v, i)) { v = fbuf[w]; i = ibuf[w]; }
+    for (int o = kWaves / 2; o >= 1; o >>= 1) {
+        const float ov = __shfl_xor(v, o);
+        const int oi = __shfl_xor(i, o);
+        if (better<kMin>(ov, oi, v, i)) { v = ov; i = oi; }
+    }
+}
+
+// register `idx` (0..15) of a 32x32 accumulator, idx not known at compile time
+__device__ __forceinline__ float acc_pick(const f32x16_t& acc, int idx)
+{
+    float v = acc[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) v = idx == r ? acc[r] : v;
+    return v;
 }
 
 // ------------------------------------------------------------------------------------
@@ -131,31 +134,29 @@ __global__ __launch_bounds__(256) void decode_init_kernel(DecodeInitArgs a)
     a.st.tok_cur[o] = 0.f;
 }
 
-// (max, sum of 2^(x - max)) pairs of an online softmax; combine is associative
-__device__ __forceinline__ void lse_combine(float& m, float& s, float om, float os)
-{
-    const float M = fmaxf(m, om);
-    const float a = m > -INFINITY ? s * exp2_fast(m - M) : 0.f;
-    const float b = om > -INFINITY ? os * exp2_fast(om - M) : 0.f;
-    m = M;
-    s = a + b;
-}
-
 // ------------------------------------------------------------------------------------
-// Dynamic LDS (floats): dot[G][budget] | rn[budget] | en[n_imp] when that fits, else the
-// same arrays live in the caller's workspace (a.lds_floats == 0).
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a)
+// One block per (batch, kv-head); kBlock = 256 for small caches (the step is a chain of short
+// dependent phases, and every instruction a wave spends on a block-wide bookkeeping step is
+// paid once per wave), 1024 for large ones (more loads in flight).
+// Dynamic LDS (floats): dot[G][budget] | rn[budget] when that fits, else the same arrays
+// live in the caller's workspace (a.lds_floats == 0).
+template <typename T, int D, int G, int kBlock>
+__global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
 {
     using P = Pack<T>;
     constexpr int kE = P::kElems;
+    constexpr int kWaves = kBlock / kWave;
     constexpr int kLpr = Tile<T, D>::kChunksPerRow;          // lanes per cache row
-    constexpr int kGroups = kDecBlock / kLpr;                // rows in flight per block
+    constexpr int kFrags = Tile<T, D>::kFrags;               // MFMA operand fragments per row
+    constexpr int kRowBytes = Tile<T, D>::kRowBytes;
+    constexpr int kUnroll = 4;                               // independent loads in flight per thread
+    constexpr int kPre = kBlock == 256 ? 2 : 1;              // row tiles in flight per wave
 
     extern __shared__ float dyn_lds[];
-    __shared__ float fbuf[kDecWaves];
-    __shared__ int ibuf[kDecWaves];
-    __shared__ float vbuf[2 * G][kDecWaves];                 // vector reductions
+    __shared__ float fbuf[kWaves];
+    __shared__ int ibuf[kWaves];
+    __shared__ float vbuf[G < 2 ? 2 : G][kWaves];            // vector reductions
+    __shared__ float sq[kWaves][32];                         // squared norms of a wave's row tile
     __shared__ float sh_self[G];                             // new query . new key (log2 units)
     __shared__ frag_t old_k[kLpr], old_v[kLpr];              // the token that leaves the window
     __shared__ float old_sc[4];                              // its norm, glo, past, cur
@@ -167,6 +168,7 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
     const int bkv = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid % kWave, wave = tid / kWave;
+    const int col = lane & 31, half = lane >> 5;             // MFMA operand row / k-half of this lane
     const int grp = tid / kLpr, piece = tid % kLpr;
 
     char* Kc = reinterpret_cast<char*>(a.st.k_cache) + (size_t)bkv * (Nb + 1) * D * sizeof(T);
@@ -181,115 +183,155 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
     float* tok_past = a.st.tok_past + (size_t)bkv * Tn;
     float* tok_cur = a.st.tok_cur + (size_t)bkv * Tn;
     const bool in_lds = a.lds_floats > 0;                    // block-uniform
-    float* stage = in_lds ? dyn_lds : a.ws + (size_t)bkv * ((size_t)(G + 1) * Nb + n_imp);
+    float* stage = in_lds ? dyn_lds : a.ws + (size_t)bkv * ((size_t)(G + 1) * Nb);
     float* dot = stage;                                      // [G][budget] q_g . cache row
     float* rn_of = stage + (size_t)G * Nb;                   // [budget] copy of row_norm
-    float* en = rn_of + Nb;                                  // [n_imp] norm of every stored entry key
     const char* qn = reinterpret_cast<const char*>(a.q_new) + (size_t)bkv * G * D * sizeof(T);
     const char* kn = reinterpret_cast<const char*>(a.k_new) + (size_t)bkv * D * sizeof(T);
     const char* vn = reinterpret_cast<const char*>(a.v_new) + (size_t)bkv * D * sizeof(T);
 
-    // ---- phase 1: one dot product per cache row and q-head, the rows' own norms -------
+    // ---- phase 1: q_g . (every cache row) as an MFMA contraction ------------------------
+    // A operand: 32 cache rows per tile (row index Nb stands for the new token's own key);
+    // B operand: the group's q-heads in columns 0..G-1, zeros elsewhere.  Lane (col = g,
+    // half) of the accumulator then holds the dots of q_g with 16 of the tile's rows.
     const int ct_mine = tid < n_imp ? entry_tok[tid] : 0;    // early: used in phase 4
-    float qf[G][kE];
+    frag_t new_k = zero_frag(), new_v = zero_frag();
+    if (grp == 0) {
+        new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
+        new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
+        float ss = frag_sumsq<T>(new_k);
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-        P::unpack(*reinterpret_cast<const frag_t*>(qn + ((size_t)g * kLpr + piece) * 16), qf[g]);
-    const frag_t new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
-    const frag_t new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
-    for (int r = tid; r < Nb; r += kDecBlock) rn_of[r] = row_norm[r];
-
-    for (int r = grp; r < Nb + 1; r += kGroups) {
-        // iteration r == Nb stands for the new token's own key
-        const frag_t fk = r < Nb ? *reinterpret_cast<const frag_t*>(Kc + ((size_t)r * kLpr + piece) * 16) : new_k;
-        float x[kE];
-        P::unpack(fk, x);
-        float d[G];
-        float ss = 0.f;
+        for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        if (piece == 0) sh_newnorm = sqrtf(ss);
+    }
+    for (int r = tid; r < Nb; r += kBlock) rn_of[r] = row_norm[r];
+    {
+        frag_t bq[kFrags];
 #pragma unroll
-        for (int g = 0; g < G; ++g) d[g] = 0.f;
+        for (int f = 0; f < kFrags; ++f)
+            bq[f] = load_frag_or_zero(qn, (size_t)col * kRowBytes + f * 32 + half * 16, col < G);
+        const int n_tiles = (Nb + 1 + 31) / 32;
+        for (int t0 = wave; t0 < n_tiles; t0 += kWaves * kPre) {
+            frag_t fa[kPre][kFrags];
 #pragma unroll
-        for (int i = 0; i < kE; ++i) {
-            ss = __builtin_fmaf(x[i], x[i], ss);
+            for (int u = 0; u < kPre; ++u) {
+                const int r = (t0 + u * kWaves) * 32 + col;
+                const char* src = r < Nb ? Kc + (size_t)r * kRowBytes : kn;
 #pragma unroll
-            for (int g = 0; g < G; ++g) d[g] = __builtin_fmaf(x[i], qf[g][i], d[g]);
-        }
+                for (int f = 0; f < kFrags; ++f) fa[u][f] = load_frag_or_zero(src, f * 32 + half * 16, r <= Nb);
+            }
 #pragma unroll
-        for (int o = kLpr / 2; o >= 1; o >>= 1) {
-            ss += __shfl_xor(ss, o);
+            for (int u = 0; u < kPre; ++u) {
+                const int t = t0 + u * kWaves;
+                if (t >= n_tiles) break;                     // wave-uniform
+                f32x16_t acc;
+                mma_first<T>(acc, fa[u][0], bq[0]);
 #pragma unroll
-            for (int g = 0; g < G; ++g) d[g] += __shfl_xor(d[g], o);
-        }
-        if (piece == 0) {
-            if (r < Nb) {
+                for (int f = 1; f < kFrags; ++f) mma<T>(acc, fa[u][f], bq[f]);
+                if (col < G) {
 #pragma unroll
-                for (int g = 0; g < G; ++g) dot[(size_t)g * Nb + r] = d[g];
-                if (r < n_imp) en[r] = sqrtf(ss);
-            } else {
-#pragma unroll
-                for (int g = 0; g < G; ++g) sh_self[g] = a.scale_log2e * d[g];
-                sh_newnorm = sqrtf(ss);
+                    for (int r16 = 0; r16 < 16; ++r16) {
+                        const int row = t * 32 + acc_row(r16, half);
+                        if (row < Nb) dot[(size_t)col * Nb + row] = acc[r16];
+                        else if (row == Nb) sh_self[col] = a.scale_log2e * acc[r16];
+                    }
+                }
             }
         }
     }
     __syncthreads();
 
     // ---- phase 2: softmax over the live tokens and the new token (Eq. 1) ---------------
-    // logit of token j in row r: scale * (|k_j| / |centre of r|) * (q . row r); one sweep
-    // keeps a running (max, sum) per q-head, a second sweep forms the weights
+    // logit of token j in row r: scale * (|k_j| / |centre of r|) * (q . row r).  Three light
+    // sweeps over the table: maxima, sums, weights.
     float m[G], sum[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) { m[g] = tid == 0 ? sh_self[g] : -INFINITY; sum[g] = tid == 0 ? 1.f : 0.f; }
-    for (int j = tid; j < Tn; j += kDecBlock) {
-        const int r = tok_row[j];
-        if (r < 0) continue;
-        const float rn = rn_of[r];
-        const float c = a.scale_log2e * (rn > 0.f ? tok_norm[j] / rn : 0.f);
+    for (int g = 0; g < G; ++g) m[g] = sh_self[g];
+    for (int j0 = tid; j0 < Tn; j0 += kBlock * kUnroll) {
+        int rr[kUnroll];
+        float tn[kUnroll];
 #pragma unroll
-        for (int g = 0; g < G; ++g) lse_combine(m[g], sum[g], c * dot[(size_t)g * Nb + r], 1.f);
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = j0 + u * kBlock;
+            rr[u] = j < Tn ? tok_row[j] : -1;
+            tn[u] = j < Tn ? tok_norm[j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int r = rr[u];
+            if (r < 0) continue;
+            const float rn = rn_of[r];
+            const float c = a.scale_log2e * (rn > 0.f ? tn[u] / rn : 0.f);
+#pragma unroll
+            for (int g = 0; g < G; ++g) m[g] = fmaxf(m[g], c * dot[(size_t)g * Nb + r]);
+        }
     }
+    block_reduce<kWaves, G, true>(m, vbuf);
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
+    for (int g = 0; g < G; ++g) sum[g] = tid == 0 ? exp2_fast(sh_self[g] - m[g]) : 0.f;
+    for (int j0 = tid; j0 < Tn; j0 += kBlock * kUnroll) {
+        int rr[kUnroll];
+        float tn[kUnroll];
 #pragma unroll
-        for (int g = 0; g < G; ++g) lse_combine(m[g], sum[g], __shfl_xor(m[g], o), __shfl_xor(sum[g], o));
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = j0 + u * kBlock;
+            rr[u] = j < Tn ? tok_row[j] : -1;
+            tn[u] = j < Tn ? tok_norm[j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int r = rr[u];
+            if (r < 0) continue;
+            const float rn = rn_of[r];
+            const float c = a.scale_log2e * (rn > 0.f ? tn[u] / rn : 0.f);
+#pragma unroll
+            for (int g = 0; g < G; ++g) sum[g] += exp2_fast(c * dot[(size_t)g * Nb + r] - m[g]);
+        }
     }
-    if (lane == 0) {
+    block_reduce<kWaves, G, false>(sum, vbuf);
 #pragma unroll
-        for (int g = 0; g < G; ++g) { vbuf[2 * g][wave] = m[g]; vbuf[2 * g + 1][wave] = sum[g]; }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        m[g] = vbuf[2 * g][lane % kDecWaves];
-        sum[g] = vbuf[2 * g + 1][lane % kDecWaves];
-#pragma unroll
-        for (int o = kDecWaves / 2; o >= 1; o >>= 1) lse_combine(m[g], sum[g], __shfl_xor(m[g], o), __shfl_xor(sum[g], o));
-        sum[g] = 1.0f / sum[g];
-    }
+    for (int g = 0; g < G; ++g) sum[g] = 1.0f / sum[g];
     // accumulate the row into s_Glo and s_Loc^cur (Sec. 3.2); the sums that Eq. 2 needs
     // (phase 4) are those of the updated scalars
-    float sg = 0.f, sl = 0.f;
-    for (int j = tid; j < Tn; j += kDecBlock) {
-        const int r = tok_row[j];
-        float w[G];
-        if (r >= 0) {
-            const float rn = rn_of[r];
-            const float c = a.scale_log2e * (rn > 0.f ? tok_norm[j] / rn : 0.f);
-            float tot = 0.f;
+    float tot2[2] = {0.f, 0.f};                              // sum of s_Glo, sum of s_Loc
+    for (int j0 = tid; j0 < Tn; j0 += kBlock * kUnroll) {
+        int rr[kUnroll];
+        float tn[kUnroll], tg[kUnroll], tp[kUnroll], tc[kUnroll];
 #pragma unroll
-            for (int g = 0; g < G; ++g) { w[g] = exp2_fast(c * dot[(size_t)g * Nb + r] - m[g]) * sum[g]; tot += w[g]; }
-            const float glo = tok_glo[j] + tot, cur = tok_cur[j] + tot;
-            tok_glo[j] = glo;
-            tok_cur[j] = cur;
-            sg += glo;
-            sl += tok_past[j] + cur;
-        } else {
-#pragma unroll
-            for (int g = 0; g < G; ++g) w[g] = 0.f;
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = j0 + u * kBlock;
+            const bool ok = j < Tn;
+            rr[u] = ok ? tok_row[j] : -1;
+            tn[u] = ok ? tok_norm[j] : 0.f;
+            tg[u] = ok ? tok_glo[j] : 0.f;
+            tp[u] = ok ? tok_past[j] : 0.f;
+            tc[u] = ok ? tok_cur[j] : 0.f;
         }
-        if (a.attn_opt) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) a.attn_opt[((size_t)bkv * G + g) * (Tn + 1) + j] = w[g];
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = j0 + u * kBlock;
+            if (j >= Tn) break;
+            const int r = rr[u];
+            float w[G];
+            if (r >= 0) {
+                const float rn = rn_of[r];
+                const float c = a.scale_log2e * (rn > 0.f ? tn[u] / rn : 0.f);
+                float tot = 0.f;
+#pragma unroll
+                for (int g = 0; g < G; ++g) { w[g] = exp2_fast(c * dot[(size_t)g * Nb + r] - m[g]) * sum[g]; tot += w[g]; }
+                const float glo = tg[u] + tot, cur = tc[u] + tot;
+                tok_glo[j] = glo;
+                tok_cur[j] = cur;
+                tot2[0] += glo;
+                tot2[1] += tp[u] + cur;
+            } else {
+#pragma unroll
+                for (int g = 0; g < G; ++g) w[g] = 0.f;
+            }
+            if (a.attn_opt) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) a.attn_opt[((size_t)bkv * G + g) * (Tn + 1) + j] = w[g];
+            }
         }
     }
     float self_tot = 0.f;                                    // every thread: same value
@@ -299,11 +341,8 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
         self_tot += w;
         if (a.attn_opt && tid == 0) a.attn_opt[((size_t)bkv * G + g) * (Tn + 1) + Tn] = w;
     }
-    if (tid == 0) { sg += self_tot; sl += self_tot; }        // the new token: glo = cur = its own weight
-    sg = wave_add(sg);
-    sl = wave_add(sl);
-    __syncthreads();                                         // vbuf free; every token's scalars written
-    if (lane == 0) { vbuf[0][wave] = sg; vbuf[1][wave] = sl; }
+    if (tid == 0) { tot2[0] += self_tot; tot2[1] += self_tot; }   // the new token: glo = cur = its own weight
+    block_reduce<kWaves, 2, false>(tot2, vbuf);              // also: every token's scalars are written
 
     // ---- phase 3: the oldest window token leaves, the new token takes its ring slot ----
     const int ring = a.step % W;
@@ -321,44 +360,70 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
         tok_glo[jo] = self_tot; tok_past[jo] = 0.f; tok_cur[jo] = self_tot;
         row_norm[ro] = sh_newnorm;
     }
-    __syncthreads();
 
     // ---- phase 4: least important class centre (Eq. 2 on the tokens' scalars) ----------
-    sg = 0.f; sl = 0.f;
-#pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) { sg += vbuf[0][w]; sl += vbuf[1][w]; }      // fixed order
-    const float align = sg > 0.f ? sl / sg : 0.f;
+    const float align = tot2[0] > 0.f ? tot2[1] / tot2[0] : 0.f;
     float bv = 0.f;
     int bi = -1;
-    for (int s = tid; s < n_imp; s += kDecBlock) {
+    for (int s = tid; s < n_imp; s += kBlock) {
         const int ct = s == tid ? ct_mine : entry_tok[s];
         const float sc = fmaxf(tok_glo[ct] * align, tok_past[ct] + tok_cur[ct]);
         if (better<true>(sc, s, bv, bi)) { bv = sc; bi = s; }
     }
-    block_arg<true>(bv, bi, fbuf, ibuf);
+    block_arg<kWaves, true>(bv, bi, fbuf, ibuf);             // its barriers also publish phase 3
     const int s_star = max(bi, 0);                           // block-uniform, in [0, n_imp)
     const int f = entry_tok[s_star];
 
     // ---- phase 5: its most similar other centre (Eq. 5, cosine of the stored keys) -----
-    float xs[kE];
-    P::unpack(*reinterpret_cast<const frag_t*>(Kc + ((size_t)s_star * kLpr + piece) * 16), xs);
-    const float en_star = en[s_star];
-    const float rn_star = en_star > 0.f ? 1.0f / en_star : 0.f;
+    // Two MFMA chains per tile of 32 entries: tile x (row s_star in every column) gives the
+    // dot products, tile x tile gives the squared norms on its diagonal.
     float cv = 0.f;
     int ci = -1;
-    for (int s = grp; s < n_imp; s += kGroups) {
-        float x[kE];
-        P::unpack(*reinterpret_cast<const frag_t*>(Kc + ((size_t)s * kLpr + piece) * 16), x);
-        float d = 0.f;
+    {
+        frag_t bs[kFrags];
+        float ss = 0.f;
 #pragma unroll
-        for (int i = 0; i < kE; ++i) d = __builtin_fmaf(x[i], xs[i], d);
+        for (int fr = 0; fr < kFrags; ++fr) {
+            bs[fr] = *reinterpret_cast<const frag_t*>(Kc + (size_t)s_star * kRowBytes + fr * 32 + half * 16);
+            ss += frag_sumsq<T>(bs[fr]);
+        }
+        ss += __shfl_xor(ss, 32);
+        const float rn_star = inv_norm(ss);
+        const int n_tiles = (n_imp + 31) / 32;
+        const int pick = col & 15;                           // the accumulator register this lane judges
+        const int my_local = acc_row(pick, half);            // ... and the tile row it belongs to
+        const bool diag_here = half == ((col >> 2) & 1);     // this lane holds |row col|^2 ...
+        const int diag_reg = 4 * (col >> 3) + (col & 3);     // ... in this register
+        for (int t0 = wave; t0 < n_tiles; t0 += kWaves * kPre) {
+            frag_t fa[kPre][kFrags];
 #pragma unroll
-        for (int o = kLpr / 2; o >= 1; o >>= 1) d += __shfl_xor(d, o);
-        const float e = en[s];
-        const float sim = (d * (e > 0.f ? 1.0f / e : 0.f)) * rn_star;
-        if (piece == 0 && s != s_star && better<false>(sim, s, cv, ci)) { cv = sim; ci = s; }
+            for (int u = 0; u < kPre; ++u) {
+                const int r = (t0 + u * kWaves) * 32 + col;
+#pragma unroll
+                for (int fr = 0; fr < kFrags; ++fr)
+                    fa[u][fr] = load_frag_or_zero(Kc, (size_t)r * kRowBytes + fr * 32 + half * 16, r < n_imp);
+            }
+#pragma unroll
+            for (int u = 0; u < kPre; ++u) {
+                const int t = t0 + u * kWaves;
+                if (t >= n_tiles) break;                     // wave-uniform
+                f32x16_t acc, acc2;
+                mma_first<T>(acc, fa[u][0], bs[0]);
+                mma_first<T>(acc2, fa[u][0], fa[u][0]);
+#pragma unroll
+                for (int fr = 1; fr < kFrags; ++fr) { mma<T>(acc, fa[u][fr], bs[fr]); mma<T>(acc2, fa[u][fr], fa[u][fr]); }
+                __builtin_amdgcn_wave_barrier();             // the previous tile's sq[] has been read
+                if (diag_here) sq[wave][col] = acc_pick(acc2, diag_reg);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const int s = t * 32 + my_local;
+                const float sim = (acc_pick(acc, pick) * inv_norm(sq[wave][my_local])) * rn_star;
+                if (col < 16 && s < n_imp && s != s_star && better<false>(sim, s, cv, ci)) { cv = sim; ci = s; }
+            }
+        }
     }
-    block_arg<false>(cv, ci, fbuf, ibuf);
+    block_arg<kWaves, false>(cv, ci, fbuf, ibuf);
     const bool merged = ci >= 0 && cv > a.tau;
     const int dst = merged ? ci : -1;
 
@@ -380,13 +445,23 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
         *reinterpret_cast<frag_t*>(Kc + ((size_t)dst * kLpr + piece) * 16) = P::pack(kb);
         *reinterpret_cast<frag_t*>(Vc + ((size_t)dst * kLpr + piece) * 16) = P::pack(vb);
     }
-    for (int j = tid; j < E; j += kDecBlock) {
-        if (tok_row[j] != s_star || j == f) continue;
-        if (merged) {
-            tok_row[j] = dst;
-        } else {
-            tok_row[j] = -1; tok_pos[j] = -1;
-            tok_norm[j] = 0.f; tok_glo[j] = 0.f; tok_past[j] = 0.f; tok_cur[j] = 0.f;
+    for (int j0 = tid; j0 < E; j0 += kBlock * kUnroll) {
+        int rr[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = j0 + u * kBlock;
+            rr[u] = j < E ? tok_row[j] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = j0 + u * kBlock;
+            if (rr[u] != s_star || j == f) continue;
+            if (merged) {
+                tok_row[j] = dst;
+            } else {
+                tok_row[j] = -1; tok_pos[j] = -1;
+                tok_norm[j] = 0.f; tok_glo[j] = 0.f; tok_past[j] = 0.f; tok_cur[j] = 0.f;
+            }
         }
     }
     __syncthreads();                                         // entry s_star fully read
@@ -409,7 +484,7 @@ __global__ __launch_bounds__(kDecBlock) void decode_step_kernel(DecodeStepArgs a
 
     // ---- phase 7: a full window of queries: s_Loc^cur becomes s_Loc^past (Sec. 3.2) ----
     if ((a.step + 1) % W == 0) {
-        for (int j = tid; j < Tn; j += kDecBlock) { tok_past[j] = tok_cur[j]; tok_cur[j] = 0.f; }
+        for (int j = tid; j < Tn; j += kBlock) { tok_past[j] = tok_cur[j]; tok_cur[j] = 0.f; }
     }
 }
 
@@ -428,19 +503,28 @@ hipError_t launch_decode_init(const DecodeInitArgs& a, bool f32, hipStream_t st)
     return a.head_dim == 64 ? launch_decode_init_t<bf16_t, 64>(a, st) : launch_decode_init_t<bf16_t, 128>(a, st);
 }
 
-template <typename T, int D>
-static hipError_t launch_decode_step_t(const DecodeStepArgs& a, hipStream_t st)
+template <typename T, int D, int kBlock>
+static hipError_t launch_decode_step_b(const DecodeStepArgs& a, hipStream_t st)
 {
-    const dim3 g(a.bkv), b(kDecBlock);
+    const dim3 g(a.bkv), b(kBlock);
     const size_t lds = sizeof(float) * (size_t)a.lds_floats;
     switch (a.group) {
-        case 1: hipLaunchKernelGGL((decode_step_kernel<T, D, 1>), g, b, lds, st, a); break;
-        case 2: hipLaunchKernelGGL((decode_step_kernel<T, D, 2>), g, b, lds, st, a); break;
-        case 4: hipLaunchKernelGGL((decode_step_kernel<T, D, 4>), g, b, lds, st, a); break;
-        case 8: hipLaunchKernelGGL((decode_step_kernel<T, D, 8>), g, b, lds, st, a); break;
+        case 1: hipLaunchKernelGGL((decode_step_kernel<T, D, 1, kBlock>), g, b, lds, st, a); break;
+        case 2: hipLaunchKernelGGL((decode_step_kernel<T, D, 2, kBlock>), g, b, lds, st, a); break;
+        case 4: hipLaunchKernelGGL((decode_step_kernel<T, D, 4, kBlock>), g, b, lds, st, a); break;
+        case 8: hipLaunchKernelGGL((decode_step_kernel<T, D, 8, kBlock>), g, b, lds, st, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_decode_step_t(const DecodeStepArgs& a, hipStream_t st)
+{
+    const int Tn = a.n_imp + a.n_tbm + a.window;
+    // f32 rows need twice the operand registers: the validation mode always takes the small block
+    if (sizeof(T) == 4 || (a.budget <= 512 && Tn <= 2048)) return launch_decode_step_b<T, D, 256>(a, st);
+    return launch_decode_step_b<T, D, 1024>(a, st);
 }
 
 hipError_t launch_decode_step(const DecodeStepArgs& a, bool f32, hipStream_t st)

@@ -308,7 +308,7 @@ static size_t decode_ws_bytes(const ems_params* p)
 {
     const size_t bkv = (size_t)p->batch * p->kv_heads;
     const size_t g = (size_t)(p->q_heads / p->kv_heads);
-    return align_up(sizeof(float) * bkv * ((g + 1) * (size_t)p->budget + (size_t)(p->budget - p->window)));
+    return align_up(sizeof(float) * bkv * (g + 1) * (size_t)p->budget);
 }
 
 static bool state_ok(const ems_decode_state* s)
@@ -375,9 +375,9 @@ int ems_decode_step(const ems_params* p, const ems_decode_state* state, int32_t 
     a.q_new = q_new; a.k_new = k_new; a.v_new = v_new;
     a.attn_opt = attn_opt; a.decision_opt = decision_opt; a.sim_opt = sim_opt;
     a.ws = static_cast<float*>(ws);
-    // per-row dot products, row norms and entry norms are staged in LDS when they fit in
+    // per-row dot products and row norms are staged in LDS when they fit in
     // what a block may ask for without raising the limit, else in the workspace
-    const size_t stage_floats = (size_t)(g + 1) * p->budget + (size_t)n_imp;
+    const size_t stage_floats = (size_t)(g + 1) * p->budget;
     a.lds_floats = stage_floats * sizeof(float) <= 60 * 1024 ? (int)stage_floats : 0;
     a.bkv = (int)bkv; a.group = g; a.head_dim = p->head_dim; a.window = p->window; a.budget = p->budget;
     a.n_imp = n_imp; a.n_tbm = n_tbm; a.step = step; a.pos_new = p->seq_len + step;

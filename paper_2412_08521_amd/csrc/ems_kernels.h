@@ -101,8 +101,8 @@ struct DecodeStepArgs {
     float* attn_opt;        // [bkv * group, T + 1] or null
     int32_t* decision_opt;  // [bkv, 2] or null
     float* sim_opt;         // [bkv] or null
-    float* ws;              // [bkv, (group + 1) * budget + n_imp] staging when it does not fit in LDS
-    int lds_floats;         // (group + 1) * budget + n_imp when staged in LDS, else 0
+    float* ws;              // [bkv, (group + 1) * budget] staging when it does not fit in LDS
+    int lds_floats;         // (group + 1) * budget when staged in LDS, else 0
     int bkv, group, head_dim, window, budget, n_imp, n_tbm, step, pos_new;
     float tau, scale_log2e;
 };
