@@ -97,6 +97,58 @@ def _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out,
     return dest, ref
 
 
+def _rel_rows(got, want):
+    rms = np.sqrt((want ** 2).mean(-1, keepdims=True))
+    return (np.abs(got - want) / np.maximum(np.abs(want), 1e-2 * np.maximum(rms, 1e-30))).max()
+
+
+def _host(d):
+    return {n_: (t_.float().cpu().numpy() if t_.is_floating_point() else t_.cpu().numpy()) for n_, t_ in d.items()}
+
+
+def _check_follow_up_calls(p, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out, units, steps=3):
+    """The entry points that follow the compression, at the configuration's full shapes:
+    shared-entry expansion, the key x value / score-weighted merge, and a few decode steps
+    (each step checked in isolation on the given (batch, kv-head) units)."""
+    from test_gpu_decode import run_and_check_step
+    rp = ref_params(p)
+    n_imp, n_tbm = B.ems_partition_sizes(p)
+    imp_n, tbm_n = imp.cpu().numpy(), tbm.cpu().numpy()
+    kf = np.concatenate([h.f32("k") for h in host])
+    vf = np.concatenate([h.f32("v") for h in host])
+    # expansion of the GPU's own compact cache
+    k_exp, v_exp, pos = B.ems_expand(p, out, tbm)
+    ho = _host(out)
+    ko, vo, po = ems_ref.expand(rp, ho["k_out"], ho["v_out"], ho["kept_pos"], tbm_n, ho["tbm_dest"], ho["k_norm"])
+    np.testing.assert_array_equal(pos.cpu().numpy(), po)
+    np.testing.assert_array_equal(v_exp.float().cpu().numpy(), vo)
+    assert _rel_rows(k_exp.float().cpu().numpy(), ko) <= 2.0 ** -8
+    # paper-faithful merge variant: redundancy = key cosine x value cosine, weights = pooled score
+    var = _host(B.ems_evict_merge_variant(p, B.EMS_SIM_KEY_VALUE, k, v, pooled, imp, tbm))
+    d_ref, s_ref, n_ref = ems_ref.dest_sim(rp, 2, kf, vf, imp_n, tbm_n)
+    np.testing.assert_allclose(var["tbm_sim"], s_ref, rtol=0, atol=1e-5)
+    assert (var["tbm_dest"] == d_ref).mean() > 0.995
+    k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge_weighted(rp, kf, vf, pooled.cpu().numpy(), imp_n, tbm_n,
+                                                             var["tbm_dest"])
+    np.testing.assert_array_equal(var["slot_count"], cnt_ref)
+    assert _rel_rows(var["k_out"], k_ref) <= RTOL_MERGE[B.EMS_BF16]
+    assert _rel_rows(var["v_out"], v_ref) <= RTOL_MERGE[B.EMS_BF16]
+    # decode steps on a copy of the cache
+    merged = {n_: t_.clone() for n_, t_ in out.items()}
+    st = B.ems_decode_init(p, merged, tbm, s_glo, s_loc)
+    rng = np.random.default_rng(5)
+    flips = 0
+    for t in range(steps):
+        qb = ems_inputs.f32_to_bf16_bits(rng.standard_normal((w.batch, w.q_heads, w.head_dim)).astype(np.float32))
+        kb = ems_inputs.f32_to_bf16_bits(rng.standard_normal((w.batch, w.kv_heads, w.head_dim)).astype(np.float32))
+        vb = ems_inputs.f32_to_bf16_bits(rng.standard_normal((w.batch, w.kv_heads, w.head_dim)).astype(np.float32))
+        flips += run_and_check_step(p, st, t, qb, kb, vb, p.tau, units, B.EMS_BF16)[0]
+    assert flips <= 1
+    live = st.tok_row >= 0
+    assert (st.tok_pos[live] >= 0).all() and torch.isfinite(st.tok_glo).all()
+    _log(f"  follow-up calls checked: expand, key x value weighted merge, {steps} decode steps on {units}")
+
+
 @pytest.mark.parametrize("mode", [B.EMS_BF16, B.EMS_F32])
 def test_config2_llama2_7b_4k_full(mode):
     """32 heads MHA, D 128, N 4096, W 32, budget 256: the oracle does the whole layer."""
@@ -166,6 +218,8 @@ def test_config4_llama3_8b_32k():
     out2 = B.ems_evict_merge(p2, k, v, imp, tbm)
     _check_properties_all_units(p2, w, host, s_glo, s_loc, imp, tbm, pooled, out2, B.EMS_BF16)
     assert (out2["slot_count"][..., -1] == 0).all()
+    _check_follow_up_calls(p2, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out2, [(0, 0), (3, 6)])
+    _check_follow_up_calls(p, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out, [(1, 3)], steps=2)
 
 
 def test_config5_extreme_128k_two_layers():
@@ -192,5 +246,6 @@ def test_config5_extreme_128k_two_layers():
             dest, _ = _check_properties_all_units(p2, w, host, s_glo, s_loc, imp, tbm, pooled, out2,
                                                   B.EMS_BF16)
             assert (dest < w.budget).any()
+            _check_follow_up_calls(p2, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out2, [(0, 2)], steps=2)
         del q, k, v, host
         torch.cuda.empty_cache()
