@@ -543,6 +543,80 @@ int ems_ref_merge_weighted(const ems_ref_params* p, const float* k, const float*
 }
 
 /* ------------------------------------------------------------------------------------
+ * Eq. 3: sparsity rate of a head.  s = Eq. 2 score (no pooling) sorted in descending
+ * order; N_k = the smallest count whose leading scores add up to at least zeta of the
+ * total; p = 1 - N_k / N.  (The equation prints the bare threshold zeta; the sentence
+ * before it says "over zeta of the total score", so the scores are taken relative to
+ * their sum.)  p_out [B,Hkv]; n_k_opt [B,Hkv] nullable.
+ * ---------------------------------------------------------------------------------- */
+static int desc_double(const void* a, const void* b)
+{
+    const double x = *(const double*)a, y = *(const double*)b;
+    return (x < y) - (x > y);
+}
+
+int ems_ref_sparsity(const ems_ref_params* p, double zeta, const double* s_glo, const double* s_loc,
+                     double* p_out, int32_t* n_k_opt)
+{
+    if (!score_params_ok(p) || !s_glo || !s_loc || !p_out) return REF_BAD;
+    if (!(zeta > 0.0) || !(zeta <= 1.0)) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len;
+    double* s = (double*)malloc(sizeof(double) * (size_t)N);
+    if (!s) return REF_BAD;
+    for (long u = 0; u < BH; ++u) {
+        const double* g = s_glo + u * N;
+        const double* l = s_loc + u * N;
+        double sg = 0.0, sl = 0.0;
+        for (long j = 0; j < N; ++j) { sg += g[j]; sl += l[j]; }
+        const double c = sg > 0.0 ? (sl / (double)N) / (sg / (double)N) : 0.0;      /* Eq. 2 */
+        double total = 0.0;
+        for (long j = 0; j < N; ++j) { s[j] = fmax(g[j] * c, l[j]); total += s[j]; }
+        qsort(s, (size_t)N, sizeof(double), desc_double);
+        double run = 0.0;
+        long nk = N;
+        for (long i = 0; i < N; ++i) {
+            run += s[i];
+            if (run >= zeta * total) { nk = i + 1; break; }
+        }
+        p_out[u] = 1.0 - (double)nk / (double)N;
+        if (n_k_opt) n_k_opt[u] = (int32_t)nk;
+    }
+    free(s);
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Eq. 4: redundancy rate of a head.  R[k][j] = cos(key_k, key_j) * cos(value_k, value_j)
+ * (Sec. 4.1); token k is redundant if some EARLIER token j < k ("another token in the
+ * existing KV cache") has R[k][j] >= tau; r = (number of redundant tokens) / N.  The first
+ * token has no predecessor.  r_out [B,Hkv]; best_opt [B,Hkv,N] = max_j<k R[k][j] (-inf for
+ * k = 0), nullable.
+ * ---------------------------------------------------------------------------------- */
+int ems_ref_redundancy(const ems_ref_params* p, const float* k, const float* v,
+                       double* r_out, double* best_opt)
+{
+    if (!score_params_ok(p) || !k || !v || !r_out) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len, D = p->head_dim;
+    for (long u = 0; u < BH; ++u) {
+        const float* Ku = k + u * N * D;
+        const float* Vu = v + u * N * D;
+        long redundant = 0;
+#pragma omp parallel for schedule(dynamic, 8) reduction(+ : redundant)
+        for (long t = 0; t < N; ++t) {
+            double best = -INFINITY;
+            for (long j = 0; j < t; ++j) {
+                const double r = cosine(Ku + t * D, Ku + j * D, D) * cosine(Vu + t * D, Vu + j * D, D);
+                if (r > best) best = r;
+            }
+            if (best_opt) best_opt[u * N + t] = best;
+            if (best >= p->tau) ++redundant;
+        }
+        r_out[u] = (double)redundant / (double)N;
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------
  * App. A, "Shared Entry Expansion": tokens that were merged share one cache entry; at
  * compute time the entry is expanded back to one key/value per token with the help of
  * the look-up-table (which entry each token went to) and the stored key norms (Sec. 4.2:

@@ -100,6 +100,17 @@ int ems_ref_merge_weighted(const ems_ref_params* p, const float* k, const float*
                            const int32_t* tbm_dest,
                            double* k_out, double* v_out, int32_t* kept_pos, int32_t* slot_count);
 
+/* Eq. 3: sparsity rate per head from the Eq. 2 score (no pooling): 1 - N_k/N with N_k the
+ * smallest number of top scores that reach zeta (0 < zeta <= 1) of the total.
+ * p_out [B,Hkv]; n_k_opt [B,Hkv] nullable. */
+int ems_ref_sparsity(const ems_ref_params* p, double zeta, const double* s_glo, const double* s_loc,
+                     double* p_out, int32_t* n_k_opt);
+
+/* Eq. 4: redundancy rate per head: share of tokens with an earlier token whose
+ * key-cosine x value-cosine reaches tau.  r_out [B,Hkv]; best_opt [B,Hkv,N] nullable. */
+int ems_ref_redundancy(const ems_ref_params* p, const float* k, const float* v,
+                       double* r_out, double* best_opt);
+
 /* Shared-entry expansion (App. A, "Shared Entry Expansion"; the position look-up-table of
  * Sec. 4.2): every kept token gets its run-time key and value back from its entry.
  * Row order per head: the N_imp centres, the N_tbm to-be-merged tokens (in tbm_idx order),

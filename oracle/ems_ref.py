@@ -258,6 +258,31 @@ def merge_weighted(p: RefParams, k, v, weight, imp_idx, tbm_idx, tbm_dest):
     return k_out, v_out, kept, cnt
 
 
+def sparsity(p: RefParams, zeta: float, s_glo, s_loc):
+    s_glo, s_loc = _f64(s_glo), _f64(s_loc)
+    shape = (p.batch, p.kv_heads, p.seq_len)
+    assert s_glo.shape == shape and s_loc.shape == shape
+    out = np.empty(shape[:2], np.float64)
+    nk = np.empty(shape[:2], np.int32)
+    cp = p.c()
+    _check(lib().ems_ref_sparsity(C.byref(cp), C.c_double(zeta), _ptr(s_glo, C.c_double),
+                                  _ptr(s_loc, C.c_double), _ptr(out, C.c_double), _ptr(nk, C.c_int32)),
+           "sparsity")
+    return out, nk
+
+
+def redundancy(p: RefParams, k, v):
+    k, v = _f32(k), _f32(v)
+    shape = (p.batch, p.kv_heads, p.seq_len, p.head_dim)
+    assert k.shape == shape and v.shape == shape
+    r = np.empty(shape[:2], np.float64)
+    best = np.empty(shape[:3], np.float64)
+    cp = p.c()
+    _check(lib().ems_ref_redundancy(C.byref(cp), _ptr(k, C.c_float), _ptr(v, C.c_float),
+                                    _ptr(r, C.c_double), _ptr(best, C.c_double)), "redundancy")
+    return r, best
+
+
 def expand(p: RefParams, k_cache, v_cache, kept_pos, tbm_idx, tbm_dest, k_norm):
     k_cache, v_cache, k_norm = _f64(k_cache), _f64(v_cache), _f64(k_norm)
     kept_pos, tbm_idx, tbm_dest = _i32(kept_pos), _i32(tbm_idx), _i32(tbm_dest)
