@@ -211,7 +211,7 @@ def main():
 
 def time_extras(args, p, w, B, torch, timed, k, v, s_glo, s_loc, imp, tbm, merged, ws_select, ws_merge):
     """Microseconds per call of ems_expand, ems_evict_merge_variant (key x value redundancy,
-    score-weighted), ems_decode_init and ems_decode_step (average over --decode-steps
+    score-weighted), ems_sparsity_rate, ems_redundancy_rate, ems_decode_init and ems_decode_step (average over --decode-steps
     consecutive generated tokens) on the workload's shapes; outputs allocated up front."""
     K = args.steps
     n_imp, n_tbm = B.ems_partition_sizes(p)
@@ -226,6 +226,8 @@ def time_extras(args, p, w, B, torch, timed, k, v, s_glo, s_loc, imp, tbm, merge
     out["evict_merge_kv_weighted"] = timed(
         lambda: B.ems_evict_merge_variant(p, B.EMS_SIM_KEY_VALUE, k, v, pooled, imp, tbm, ws=ws_merge,
                                           out=outs2), K) * 1e3
+    out["sparsity_rate"] = timed(lambda: B.ems_sparsity_rate(p, 0.9, s_glo, s_loc), K) * 1e3
+    out["redundancy_rate"] = timed(lambda: B.ems_redundancy_rate(p, k, v), max(1, K // 5)) * 1e3
     g = p.q_heads // p.kv_heads
     if g in (1, 2, 4, 8):
         B.ems_evict_merge(p, k, v, imp, tbm, ws=ws_merge, out=outs2)     # a cache the steps may overwrite

@@ -222,6 +222,32 @@ int ems_expand(const ems_params* p, const void* k_cache, const void* v_cache,
                void* hip_stream);
 
 /*
+ * Per-head statistics of Sec. 4.1 (diagnostics: they motivate the method, the compression
+ * itself does not need them).
+ *
+ * ems_sparsity_rate -- Eq. 3.  With s the Eq. 2 score of the head (ems_select's formula, no
+ * pooling) sorted in descending order and N_k the smallest count whose leading scores add up
+ * to at least zeta of the total, rate = 1 - N_k / N.
+ *   zeta        0 < zeta <= 1
+ *   s_glo, s_loc in : device [B, Hkv, N] f32
+ *   rate        out: device [B, Hkv] f32
+ *   n_k_opt     out: device [B, Hkv] i32, or NULL
+ * Masses are compared in 40-bit fixed point relative to the total, so N_k can differ from an
+ * exact evaluation where the threshold is met to within 1e-6 of the total.  No workspace.
+ *
+ * ems_redundancy_rate -- Eq. 4.  R[t][j] = cos(k_t, k_j) * cos(v_t, v_j); token t is redundant
+ * if an EARLIER token j < t has R[t][j] >= tau; rate = redundant tokens / N.
+ *   k, v        in : device [B, Hkv, N, D] `dtype`
+ *   rate        out: device [B, Hkv] f32
+ *   best        out: device [B, Hkv, N] f32: max over j < t of R[t][j] (-inf for t = 0)
+ * O(N^2 D) work per head.  No workspace.  Uses tau, batch, kv_heads, head_dim, seq_len, dtype.
+ */
+int ems_sparsity_rate(const ems_params* p, float zeta, const float* s_glo, const float* s_loc,
+                      float* rate, int32_t* n_k_opt, void* hip_stream);
+int ems_redundancy_rate(const ems_params* p, const void* k, const void* v,
+                        float* rate, float* best, void* hip_stream);
+
+/*
  * Decode-time state of one layer's compressed cache (Sec. 3.2, decoding paragraph; Sec. 5
  * "Memory analysis": besides the budget-sized cache, one scalar per kept token for s_Glo,
  * s_Loc^past, s_Loc^cur, the key norm and the position look-up-table).  Every member is a

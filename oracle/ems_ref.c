@@ -616,6 +616,33 @@ int ems_ref_redundancy(const ems_ref_params* p, const float* k, const float* v,
     return REF_OK;
 }
 
+/* Eq. 4's inner maximum for chosen tokens only (the same loop as ems_ref_redundancy, for
+ * sequences where all N^2/2 pairs are too many): best_out[u][i] = max_j<t R[t][j] with
+ * t = tokens[i], for every (batch, kv-head) unit u.  best_out [B,Hkv,n_tokens]. */
+int ems_ref_redundancy_at(const ems_ref_params* p, const float* k, const float* v,
+                          const int32_t* tokens, int32_t n_tokens, double* best_out)
+{
+    if (!score_params_ok(p) || !k || !v || !tokens || n_tokens < 0 || !best_out) return REF_BAD;
+    const long BH = (long)p->batch * p->kv_heads, N = p->seq_len, D = p->head_dim;
+    for (long i = 0; i < n_tokens; ++i)
+        if (tokens[i] < 0 || tokens[i] >= N) return REF_BAD;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long u = 0; u < BH; ++u) {
+        for (long i = 0; i < n_tokens; ++i) {
+            const float* Ku = k + u * N * D;
+            const float* Vu = v + u * N * D;
+            const long t = tokens[i];
+            double best = -INFINITY;
+            for (long j = 0; j < t; ++j) {
+                const double r = cosine(Ku + t * D, Ku + j * D, D) * cosine(Vu + t * D, Vu + j * D, D);
+                if (r > best) best = r;
+            }
+            best_out[u * n_tokens + i] = best;
+        }
+    }
+    return REF_OK;
+}
+
 /* ------------------------------------------------------------------------------------
  * App. A, "Shared Entry Expansion": tokens that were merged share one cache entry; at
  * compute time the entry is expanded back to one key/value per token with the help of

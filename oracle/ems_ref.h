@@ -111,6 +111,10 @@ int ems_ref_sparsity(const ems_ref_params* p, double zeta, const double* s_glo, 
 int ems_ref_redundancy(const ems_ref_params* p, const float* k, const float* v,
                        double* r_out, double* best_opt);
 
+/* The inner maximum of Eq. 4 for chosen tokens only: best_out [B,Hkv,n_tokens]. */
+int ems_ref_redundancy_at(const ems_ref_params* p, const float* k, const float* v,
+                          const int32_t* tokens, int32_t n_tokens, double* best_out);
+
 /* Shared-entry expansion (App. A, "Shared Entry Expansion"; the position look-up-table of
  * Sec. 4.2): every kept token gets its run-time key and value back from its entry.
  * Row order per head: the N_imp centres, the N_tbm to-be-merged tokens (in tbm_idx order),

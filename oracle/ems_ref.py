@@ -283,6 +283,18 @@ def redundancy(p: RefParams, k, v):
     return r, best
 
 
+def redundancy_at(p: RefParams, k, v, tokens):
+    k, v, tokens = _f32(k), _f32(v), _i32(tokens)
+    shape = (p.batch, p.kv_heads, p.seq_len, p.head_dim)
+    assert k.shape == shape and v.shape == shape and tokens.ndim == 1
+    best = np.empty((p.batch, p.kv_heads, len(tokens)), np.float64)
+    cp = p.c()
+    _check(lib().ems_ref_redundancy_at(C.byref(cp), _ptr(k, C.c_float), _ptr(v, C.c_float),
+                                       _ptr(tokens, C.c_int32), C.c_int32(len(tokens)),
+                                       _ptr(best, C.c_double)), "redundancy_at")
+    return best
+
+
 def expand(p: RefParams, k_cache, v_cache, kept_pos, tbm_idx, tbm_dest, k_norm):
     k_cache, v_cache, k_norm = _f64(k_cache), _f64(v_cache), _f64(k_norm)
     kept_pos, tbm_idx, tbm_dest = _i32(kept_pos), _i32(tbm_idx), _i32(tbm_dest)

@@ -7,5 +7,6 @@ from .binding import (EMS_BF16, EMS_F32, EMS_SIM_KEY, EMS_SIM_KEY_VALUE,  # noqa
                       EMS_SIM_VALUE, DecodeState, EmsError, EmsParams, ems_attention_lse,
                       ems_decode_init, ems_decode_step, ems_decode_workspace_bytes,
                       ems_evict_merge, ems_evict_merge_variant, ems_expand, ems_global_local_score,
-                      ems_global_local_score_from_lse, ems_partition_sizes, ems_select,
+                      ems_global_local_score_from_lse, ems_partition_sizes, ems_redundancy_rate, ems_select,
+                      ems_sparsity_rate,
                       ems_version, ems_workspace_bytes)

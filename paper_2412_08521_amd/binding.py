@@ -29,7 +29,8 @@ EMS_SIM_KEY_VALUE = 2
 EXPORTS = ("ems_version", "ems_strerror", "ems_partition_sizes", "ems_workspace_bytes",
            "ems_global_local_score", "ems_attention_lse", "ems_global_local_score_from_lse",
            "ems_select", "ems_evict_merge", "ems_evict_merge_variant", "ems_expand",
-           "ems_decode_workspace_bytes", "ems_decode_init", "ems_decode_step")
+           "ems_decode_workspace_bytes", "ems_decode_init", "ems_decode_step",
+           "ems_sparsity_rate", "ems_redundancy_rate")
 
 
 class ems_params(C.Structure):
@@ -101,6 +102,8 @@ def lib():
         l.ems_evict_merge.argtypes = [P] + [C.c_void_p] * 12 + [C.c_size_t, C.c_void_p]
         l.ems_evict_merge_variant.argtypes = ([P, C.c_int] + [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p])
         l.ems_expand.argtypes = [P] + [C.c_void_p] * 10
+        l.ems_sparsity_rate.argtypes = [P, C.c_float] + [C.c_void_p] * 5
+        l.ems_redundancy_rate.argtypes = [P] + [C.c_void_p] * 5
         S = C.POINTER(ems_decode_state)
         l.ems_decode_workspace_bytes.argtypes = [P, C.POINTER(C.c_size_t)]
         l.ems_decode_init.argtypes = [P] + [C.c_void_p] * 7 + [S, C.c_void_p]
@@ -416,3 +419,32 @@ def ems_decode_step(p: EmsParams, st: DecodeState, step: int, q_new, k_new, v_ne
     if rc != EMS_OK:
         raise EmsError(rc, "ems_decode_step")
     return out
+
+
+def ems_sparsity_rate(p: EmsParams, zeta: float, s_glo, s_loc):
+    """Eq. 3 -> (rate [B,Hkv] f32, n_k [B,Hkv] i32)."""
+    shape = (p.batch, p.kv_heads, p.seq_len)
+    _check_tensor(s_glo, shape, torch.float32, "s_glo")
+    _check_tensor(s_loc, shape, torch.float32, "s_loc")
+    rate = torch.empty(shape[:2], dtype=torch.float32, device=s_glo.device)
+    n_k = torch.empty(shape[:2], dtype=torch.int32, device=s_glo.device)
+    cp = p.c()
+    rc = lib().ems_sparsity_rate(C.byref(cp), float(zeta), _ptr(s_glo), _ptr(s_loc), _ptr(rate), _ptr(n_k),
+                                 _stream())
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_sparsity_rate")
+    return rate, n_k
+
+
+def ems_redundancy_rate(p: EmsParams, k, v):
+    """Eq. 4 -> (rate [B,Hkv] f32, best [B,Hkv,N] f32)."""
+    shape = (p.batch, p.kv_heads, p.seq_len, p.head_dim)
+    _check_tensor(k, shape, p.torch_dtype, "k")
+    _check_tensor(v, shape, p.torch_dtype, "v")
+    rate = torch.empty(shape[:2], dtype=torch.float32, device=k.device)
+    best = torch.empty(shape[:3], dtype=torch.float32, device=k.device)
+    cp = p.c()
+    rc = lib().ems_redundancy_rate(C.byref(cp), _ptr(k), _ptr(v), _ptr(rate), _ptr(best), _stream())
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_redundancy_rate")
+    return rate, best

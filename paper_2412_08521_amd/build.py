@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 OBJ_DIR = os.path.join(_HERE, "_build")
 LIB = os.path.join(_HERE, "libems_hip.so")
-SOURCES = ["ems_api.hip", "score.hip", "select.hip", "merge.hip", "decode.hip"]
+SOURCES = ["ems_api.hip", "score.hip", "select.hip", "merge.hip", "decode.hip", "stats.hip"]
 HEADERS = ["ems_common.h", "ems_kernels.h", "ems_rows.h", os.path.join("..", "..", "include", "ems.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -296,6 +296,32 @@ int ems_expand(const ems_params* p, const void* k_cache, const void* v_cache,
     return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
 }
 
+int ems_sparsity_rate(const ems_params* p, float zeta, const float* s_glo, const float* s_loc,
+                      float* rate, int32_t* n_k_opt, void* hip_stream)
+{
+    int why;
+    if (!score_params_ok(p, &why)) return why;
+    if (!s_glo || !s_loc || !rate || !(zeta > 0.f) || !(zeta <= 1.f)) return EMS_ERR_INVALID_ARG;
+    ems::StatsArgs a{};
+    a.s_glo = s_glo; a.s_loc = s_loc; a.p_out = rate; a.n_k_opt = n_k_opt;
+    a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len; a.zeta = zeta;
+    const hipError_t e = ems::launch_sparsity(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
+int ems_redundancy_rate(const ems_params* p, const void* k, const void* v,
+                        float* rate, float* best, void* hip_stream)
+{
+    int why;
+    if (!score_params_ok(p, &why)) return why;
+    if (!k || !v || !rate || !best || std::isnan(p->tau)) return EMS_ERR_INVALID_ARG;
+    ems::StatsArgs a{};
+    a.k = k; a.v = v; a.r_out = rate; a.best = best;
+    a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len; a.tau = p->tau;
+    const hipError_t e = ems::launch_redundancy(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
 static bool decode_params_ok(const ems_params* p, int* why)
 {
     if (!full_params_ok(p, why)) return false;

@@ -107,7 +107,22 @@ struct DecodeStepArgs {
     float tau, scale_log2e;
 };
 
+struct StatsArgs {
+    const float* s_glo;     // [bkv, seq_len]   (sparsity)
+    const float* s_loc;
+    float* p_out;           // [bkv]
+    int32_t* n_k_opt;       // [bkv] or null
+    const void* k;          // [bkv, seq_len, D] (redundancy)
+    const void* v;
+    float* r_out;           // [bkv]
+    float* best;            // [bkv, seq_len]
+    int bkv, head_dim, seq_len;
+    float zeta, tau;
+};
+
 int score_keys_per_block(int dtype_is_f32);
+hipError_t launch_sparsity(const StatsArgs& a, hipStream_t st);
+hipError_t launch_redundancy(const StatsArgs& a, bool f32, hipStream_t st);
 hipError_t launch_decode_init(const DecodeInitArgs& a, bool f32, hipStream_t st);
 hipError_t launch_decode_step(const DecodeStepArgs& a, bool f32, hipStream_t st);
 hipError_t launch_expand(const ExpandArgs& a, bool f32, hipStream_t st);

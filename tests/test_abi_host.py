@@ -136,3 +136,16 @@ def test_decode_argument_errors(lib):
     assert lib.ems_decode_step(C.byref(odd), C.byref(st), 0, d, d, d, None, None, None, d, 1 << 30, None) == B.EMS_ERR_UNSUPPORTED
     n = C.c_size_t(0)
     assert lib.ems_decode_workspace_bytes(C.byref(odd), C.byref(n)) == B.EMS_ERR_UNSUPPORTED
+
+
+def test_stats_argument_errors(lib):
+    cp = _bad().c()
+    d = C.c_void_p(256)
+    for zeta in (0.0, -0.1, 1.5, float("nan")):
+        assert lib.ems_sparsity_rate(C.byref(cp), zeta, d, d, d, None, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_sparsity_rate(C.byref(cp), 0.9, None, d, d, None, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_sparsity_rate(C.byref(cp), 0.9, d, d, None, None, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_redundancy_rate(C.byref(cp), d, d, d, None, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_redundancy_rate(C.byref(cp), None, d, d, d, None) == B.EMS_ERR_INVALID_ARG
+    odd = _bad(head_dim=96).c()
+    assert lib.ems_redundancy_rate(C.byref(odd), d, d, d, d, None) == B.EMS_ERR_UNSUPPORTED

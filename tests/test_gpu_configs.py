@@ -133,6 +133,17 @@ def _check_follow_up_calls(p, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out
     np.testing.assert_array_equal(var["slot_count"], cnt_ref)
     assert _rel_rows(var["k_out"], k_ref) <= RTOL_MERGE[B.EMS_BF16]
     assert _rel_rows(var["v_out"], v_ref) <= RTOL_MERGE[B.EMS_BF16]
+    # per-head statistics: Eq. 3 against the oracle on the GPU's own scores, Eq. 4 on sampled tokens
+    rate, nk = B.ems_sparsity_rate(p, 0.9, s_glo, s_loc)
+    o_rate, o_nk = ems_ref.sparsity(rp, 0.9, s_glo.cpu().numpy(), s_loc.cpu().numpy())
+    assert np.abs(nk.cpu().numpy() - o_nk).max() <= max(2, w.seq_len // 2000), (nk, o_nk)
+    red, best = B.ems_redundancy_rate(p, k, v)
+    tokens = np.array([0, 1, 31, 32, 1000, w.seq_len // 2 + 17, w.seq_len - 1], np.int32)
+    o_best = ems_ref.redundancy_at(rp, kf, vf, tokens)
+    np.testing.assert_allclose(best.cpu().numpy()[..., tokens][..., 1:], o_best[..., 1:], rtol=0, atol=1e-5)
+    assert (best[..., 0] == -np.inf).all()
+    np.testing.assert_array_equal(np.rint(red.cpu().numpy() * w.seq_len),
+                                  (best >= p.tau).sum(-1).cpu().numpy())
     # decode steps on a copy of the cache
     merged = {n_: t_.clone() for n_, t_ in out.items()}
     st = B.ems_decode_init(p, merged, tbm, s_glo, s_loc)
@@ -146,7 +157,8 @@ def _check_follow_up_calls(p, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out
     assert flips <= 1
     live = st.tok_row >= 0
     assert (st.tok_pos[live] >= 0).all() and torch.isfinite(st.tok_glo).all()
-    _log(f"  follow-up calls checked: expand, key x value weighted merge, {steps} decode steps on {units}")
+    _log(f"  follow-up calls checked: expand, key x value weighted merge, Eq. 3 / Eq. 4 statistics, "
+         f"{steps} decode steps on {units}")
 
 
 @pytest.mark.parametrize("mode", [B.EMS_BF16, B.EMS_F32])

@@ -130,3 +130,14 @@ def test_redundancy_threshold_extremes_and_inclusive_comparison():
     above = ems_ref.redundancy(_p(n, d=d, tau=float(np.nextafter(best[0, 0, t], 2.0))), k, v)[0][0, 0]
     np.testing.assert_allclose(at, 1 / n)
     assert above == 0.0
+
+
+def test_redundancy_at_is_the_same_loop_on_chosen_tokens():
+    n, h, d = 70, 2, 16
+    inp = ems_inputs.small(1, h, h, d, n, seed=6)
+    k, v = inp.f32("k"), inp.f32("v")
+    _, best = ems_ref.redundancy(_p(n, h=h, d=d), k, v)
+    tokens = np.array([0, 1, 17, 69], np.int32)
+    np.testing.assert_array_equal(ems_ref.redundancy_at(_p(n, h=h, d=d), k, v, tokens), best[..., tokens])
+    with pytest.raises(ValueError):
+        ems_ref.redundancy_at(_p(n, h=h, d=d), k, v, np.array([70], np.int32))
