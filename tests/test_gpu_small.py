@@ -462,3 +462,48 @@ def test_all_zero_weights_keep_the_centres_on_gpu():
         assert torch.equal(o["k_out"][0, h, :n_imp], k[0, h, i_d[0, h].long()])
         assert torch.equal(o["v_out"][0, h, :n_imp], v[0, h, i_d[0, h].long()])
     assert (o["slot_count"][..., :n_imp].sum(-1) == n_imp + (o["tbm_dest"] < n_imp).sum(-1)).all()
+
+
+# ---------------------------------------------------------------------------- degenerate inputs
+@pytest.mark.parametrize("mode", MODES)
+def test_zero_keys_identical_keys_and_full_budget(mode):
+    """Keys of norm 0 have similarity 0 and unit key 0; identical keys tie and go to the lowest
+    slot; budget = N leaves nothing to merge or evict."""
+    b, hkv, d, n, w, nb, r = 1, 2, 64, 400, 8, 40, 2.0
+    inp = ems_inputs.small(b, hkv, hkv, d, n, seed=31)
+    kf = inp.f32("k").copy()
+    p = B.EmsParams(b, hkv, hkv, d, n, w, nb, merge_ratio=r, tau=-0.5, dtype=mode)
+    imp, tbm = _random_partition(p, seed=32)
+    kf[0, 0, tbm[0, 0, 3]] = 0.0                         # a to-be-merged key of norm 0
+    kf[0, 0, imp[0, 0, 5]] = 0.0                         # a centre of norm 0
+    kf[0, 1, :] = kf[0, 1, 0]                            # head 1: every key the same
+    inp.k = ems_inputs.f32_to_bf16_bits(kf)
+    kf, vf = inp.f32("k"), inp.f32("v")
+    out = B.ems_evict_merge(p, dev_tensor(inp.k, mode), dev_tensor(inp.v, mode),
+                            torch.from_numpy(imp).cuda(), torch.from_numpy(tbm).cuda())
+    out = {k_: v_.float().cpu().numpy() if v_.is_floating_point() else v_.cpu().numpy() for k_, v_ in out.items()}
+    rp = ref_params(p)
+    ref = ems_ref.evict_merge(rp, kf, vf, imp, tbm)
+    assert out["tbm_sim"][0, 0, 3] == 0.0 and out["k_norm"][0, 0, p.budget - w + 3] == 0.0
+    np.testing.assert_allclose(out["tbm_sim"][0, 0], ref["tbm_sim"][0, 0], atol=5e-6)
+    # head 1: all cosines are 1 up to rounding, so any slot is within noise; the merged rows must
+    # still be the oracle's average for the kernel's own destinations
+    np.testing.assert_allclose(out["tbm_sim"][0, 1], 1.0, atol=5e-6)
+    k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge(rp, kf, vf, imp, tbm, out["tbm_dest"])
+    np.testing.assert_array_equal(out["slot_count"], cnt_ref)
+    for name, want in (("k_out", k_ref), ("v_out", v_ref)):
+        rms = np.sqrt((want ** 2).mean(-1, keepdims=True))
+        err = np.abs(out[name] - want) / np.maximum(np.abs(want), 1e-2 * np.maximum(rms, 1e-30))
+        assert err.max() <= RTOL_MERGE[mode], f"{name}: {err.max():.3e}"
+    assert np.isfinite(out["k_out"]).all() and np.isfinite(out["v_out"]).all()
+
+    # budget = N: every position before the window is a centre, nothing is merged or evicted
+    p2 = B.EmsParams(b, hkv, hkv, d, n, w, n, merge_ratio=3.0, tau=0.6, dtype=mode)
+    assert B.ems_partition_sizes(p2) == (n - w, 0)
+    s = torch.rand((b, hkv, n), device="cuda")
+    imp2, tbm2 = B.ems_select(p2, s, s.clone())
+    assert torch.equal(imp2, torch.arange(n - w, device="cuda", dtype=torch.int32).expand(b, hkv, -1))
+    kd, vd = dev_tensor(inp.k, mode), dev_tensor(inp.v, mode)
+    o2 = B.ems_evict_merge(p2, kd, vd, imp2, tbm2)
+    assert torch.equal(o2["k_out"][:, :, :n], kd) and torch.equal(o2["v_out"][:, :, :n], vd)
+    assert (o2["slot_count"][..., :-1] == 1).all() and (o2["slot_count"][..., -1] == 0).all()
