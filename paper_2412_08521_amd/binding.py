@@ -356,18 +356,24 @@ class DecodeState:
         dev = k_cache.device
         _check_tensor(k_cache, (B, H, Nb + 1, p.head_dim), p.torch_dtype, "k_cache")
         _check_tensor(v_cache, (B, H, Nb + 1, p.head_dim), p.torch_dtype, "v_cache")
-        i32, f32 = torch.int32, torch.float32
         self.n_tokens = T
         self.k_cache, self.v_cache = k_cache, v_cache
-        self.row_norm = torch.zeros((B, H, Nb), dtype=f32, device=dev)
-        self.entry_count = torch.zeros((B, H, n_imp), dtype=i32, device=dev)
-        self.entry_tok = torch.zeros((B, H, n_imp), dtype=i32, device=dev)
-        self.tok_pos = torch.full((B, H, T), -1, dtype=i32, device=dev)
-        self.tok_row = torch.full((B, H, T), -1, dtype=i32, device=dev)
-        self.tok_norm = torch.zeros((B, H, T), dtype=f32, device=dev)
-        self.tok_glo = torch.zeros((B, H, T), dtype=f32, device=dev)
-        self.tok_past = torch.zeros((B, H, T), dtype=f32, device=dev)
-        self.tok_cur = torch.zeros((B, H, T), dtype=f32, device=dev)
+        # one slab for the nine small arrays: they are all touched by every step, and sitting in
+        # one allocation keeps them on as few pages as possible
+        shapes = [("row_norm", (B, H, Nb), torch.float32), ("entry_count", (B, H, n_imp), torch.int32),
+                  ("entry_tok", (B, H, n_imp), torch.int32), ("tok_pos", (B, H, T), torch.int32),
+                  ("tok_row", (B, H, T), torch.int32), ("tok_norm", (B, H, T), torch.float32),
+                  ("tok_glo", (B, H, T), torch.float32), ("tok_past", (B, H, T), torch.float32),
+                  ("tok_cur", (B, H, T), torch.float32)]
+        sizes = [(4 * int(torch.Size(shape).numel()) + 255) // 256 * 256 for _, shape, _ in shapes]
+        self.slab = torch.zeros(sum(sizes), dtype=torch.uint8, device=dev)
+        off = 0
+        for (name, shape, dtype), size in zip(shapes, sizes):
+            n = int(torch.Size(shape).numel())
+            setattr(self, name, self.slab[off:off + 4 * n].view(dtype).view(shape))
+            off += size
+        self.tok_pos.fill_(-1)
+        self.tok_row.fill_(-1)
 
     def c(self) -> ems_decode_state:
         if getattr(self, "_c", None) is None:                # the tensors never move

@@ -16,21 +16,54 @@
 
 namespace ems {
 
-// ---- block-wide reductions over kWaves waves.  Every thread of the block must call; the
-// result is identical in every thread (the combines are commutative, so the butterflies
-// give every lane the same value).
+// ---- wave and block reductions.  Inside a wave the combine runs on DPP lane permutations
+// (xor 1, xor 2 inside quads, then the half-row and row mirrors), which have ALU latency;
+// the four row results are then read through scalar registers, so the result is uniform.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, false));
+}
+template <int kCtrl>
+__device__ __forceinline__ int dpp_i(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
+
+template <bool kMax> __device__ __forceinline__ float comb(float a, float b) { return kMax ? fmaxf(a, b) : a + b; }
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+// all 16 lanes of every row end up with their row's result
+template <bool kMax>
+__device__ __forceinline__ float row_reduce(float v)
+{
+    v = comb<kMax>(v, dpp_f<kDppXor1>(v));
+    v = comb<kMax>(v, dpp_f<kDppXor2>(v));
+    v = comb<kMax>(v, dpp_f<kDppHalfMirror>(v));
+    v = comb<kMax>(v, dpp_f<kDppMirror>(v));
+    return v;
+}
+template <bool kMax>
+__device__ __forceinline__ float wave_reduce(float v)
+{
+    v = row_reduce<kMax>(v);
+    return comb<kMax>(comb<kMax>(lane_value(v, 0), lane_value(v, 16)), comb<kMax>(lane_value(v, 32), lane_value(v, 48)));
+}
+
+// Every thread of the block must call; the result is identical in every thread.
 template <int kWaves, int kN, bool kMax>
 __device__ __forceinline__ void block_reduce(float (&v)[kN], float (*buf)[kWaves])
 {
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-#pragma unroll
-        for (int i = 0; i < kN; ++i) {
-            const float x = __shfl_xor(v[i], o);
-            v[i] = kMax ? fmaxf(v[i], x) : v[i] + x;
-        }
-    }
+    for (int i = 0; i < kN; ++i) v[i] = wave_reduce<kMax>(v[i]);
     __syncthreads();                                    // buf free again
     if (lane == 0) {
 #pragma unroll
@@ -39,11 +72,13 @@ __device__ __forceinline__ void block_reduce(float (&v)[kN], float (*buf)[kWaves
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kN; ++i) {
-        v[i] = buf[i][lane % kWaves];
+        if constexpr (kWaves == 16) {
+            v[i] = lane_value(row_reduce<kMax>(buf[i][lane & 15]), 0);
+        } else {
+            float r = buf[i][0];
 #pragma unroll
-        for (int o = kWaves / 2; o >= 1; o >>= 1) {
-            const float x = __shfl_xor(v[i], o);
-            v[i] = kMax ? fmaxf(v[i], x) : v[i] + x;
+            for (int w = 1; w < kWaves; ++w) r = comb<kMax>(r, buf[i][w]);       // fixed order
+            v[i] = r;
         }
     }
 }
@@ -56,25 +91,49 @@ __device__ __forceinline__ bool better(float v, int i, float bv, int bi)
     if (kMin ? v < bv : v > bv) return true;
     return v == bv && i < bi;
 }
+template <bool kMin, int kCtrl>
+__device__ __forceinline__ void arg_step(float& v, int& i)
+{
+    const float ov = dpp_f<kCtrl>(v);
+    const int oi = dpp_i<kCtrl>(i);
+    if (better<kMin>(ov, oi, v, i)) { v = ov; i = oi; }
+}
+template <bool kMin>
+__device__ __forceinline__ void row_arg(float& v, int& i)
+{
+    arg_step<kMin, kDppXor1>(v, i);
+    arg_step<kMin, kDppXor2>(v, i);
+    arg_step<kMin, kDppHalfMirror>(v, i);
+    arg_step<kMin, kDppMirror>(v, i);
+}
 template <int kWaves, bool kMin>
 __device__ __forceinline__ void block_arg(float& v, int& i, float* fbuf, int* ibuf)
 {
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    row_arg<kMin>(v, i);
+    {
+        float bv = lane_value(v, 0);
+        int bi = __builtin_amdgcn_readlane(i, 0);
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        const float ov = __shfl_xor(v, o);
-        const int oi = __shfl_xor(i, o);
-        if (better<kMin>(ov, oi, v, i)) { v = ov; i = oi; }
+        for (int r = 16; r < 64; r += 16) {
+            const float ov = lane_value(v, r);
+            const int oi = __builtin_amdgcn_readlane(i, r);
+            if (better<kMin>(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        v = bv; i = bi;
     }
     __syncthreads();
     if (lane == 0) { fbuf[wave] = v; ibuf[wave] = i; }
     __syncthreads();
-    v = fbuf[lane % kWaves]; i = ibuf[lane % kWaves];
+    if constexpr (kWaves == 16) {
+        v = fbuf[lane & 15]; i = ibuf[lane & 15];
+        row_arg<kMin>(v, i);
+        v = lane_value(v, 0); i = __builtin_amdgcn_readlane(i, 0);
+    } else {
+        v = fbuf[0]; i = ibuf[0];
 #pragma unroll
-    for (int o = kWaves / 2; o >= 1; o >>= 1) {
-        const float ov = __shfl_xor(v, o);
-        const int oi = __shfl_xor(i, o);
-        if (better<kMin>(ov, oi, v, i)) { v = ov; i = oi; }
+        for (int w = 1; w < kWaves; ++w)
+            if (better<kMin>(fbuf[w], ibuf[w], v, i)) { v = fbuf[w]; i = ibuf[w]; }
     }
 }
 
@@ -151,6 +210,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     constexpr int kRowBytes = Tile<T, D>::kRowBytes;
     constexpr int kUnroll = 4;                               // independent loads in flight per thread
     constexpr int kPre = kBlock == 256 ? 2 : 1;              // row tiles in flight per wave
+    constexpr bool kPreload = kBlock == 256;                 // first batch of table elements fetched up front
 
     extern __shared__ float dyn_lds[];
     __shared__ float fbuf[kWaves];
@@ -194,25 +254,22 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     // A operand: 32 cache rows per tile (row index Nb stands for the new token's own key);
     // B operand: the group's q-heads in columns 0..G-1, zeros elsewhere.  Lane (col = g,
     // half) of the accumulator then holds the dots of q_g with 16 of the tile's rows.
-    const int ct_mine = tid < n_imp ? entry_tok[tid] : 0;    // early: used in phase 4
+    // Everything this thread will need from global memory that does not depend on earlier
+    // phases is requested here, behind the first tile's loads, so that the round trips overlap:
+    // the first batch of table elements (all of them for small tables), the centre token of
+    // "its" entry, its share of the row norms, the new token's row.
+    const int ct_mine = tid < n_imp ? entry_tok[tid] : 0;    // used in phase 4
     frag_t new_k = zero_frag(), new_v = zero_frag();
-    if (grp == 0) {
-        new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
-        new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
-        float ss = frag_sumsq<T>(new_k);
-#pragma unroll
-        for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
-        if (piece == 0) sh_newnorm = sqrtf(ss);
-    }
-    for (int r = tid; r < Nb; r += kBlock) rn_of[r] = row_norm[r];
+    int pre_rr[kUnroll];
+    float pre_tn[kUnroll], pre_tg[kUnroll], pre_tp[kUnroll], pre_tc[kUnroll];
     {
         frag_t bq[kFrags];
 #pragma unroll
         for (int f = 0; f < kFrags; ++f)
             bq[f] = load_frag_or_zero(qn, (size_t)col * kRowBytes + f * 32 + half * 16, col < G);
         const int n_tiles = (Nb + 1 + 31) / 32;
-        for (int t0 = wave; t0 < n_tiles; t0 += kWaves * kPre) {
-            frag_t fa[kPre][kFrags];
+        frag_t fa[kPre][kFrags];
+        auto load_tiles = [&](int t0) {
 #pragma unroll
             for (int u = 0; u < kPre; ++u) {
                 const int r = (t0 + u * kWaves) * 32 + col;
@@ -220,6 +277,26 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
 #pragma unroll
                 for (int f = 0; f < kFrags; ++f) fa[u][f] = load_frag_or_zero(src, f * 32 + half * 16, r <= Nb);
             }
+        };
+        load_tiles(wave);
+        // (behind the first tiles in the memory queue)
+#pragma unroll
+        for (int u = 0; u < (kPreload ? kUnroll : 0); ++u) {
+            const int j = tid + u * kBlock;
+            const bool ok = j < Tn;
+            pre_rr[u] = ok ? tok_row[j] : -1;
+            pre_tn[u] = ok ? tok_norm[j] : 0.f;
+            pre_tg[u] = ok ? tok_glo[j] : 0.f;
+            pre_tp[u] = ok ? tok_past[j] : 0.f;
+            pre_tc[u] = ok ? tok_cur[j] : 0.f;
+        }
+        const float rn_mine = tid < Nb ? row_norm[tid] : 0.f;
+        if (grp == 0) {
+            new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
+            new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
+        }
+        for (int t0 = wave; t0 < n_tiles; t0 += kWaves * kPre) {
+            if (t0 != wave) load_tiles(t0);
 #pragma unroll
             for (int u = 0; u < kPre; ++u) {
                 const int t = t0 + u * kWaves;
@@ -238,6 +315,14 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
                 }
             }
         }
+        if (tid < Nb) rn_of[tid] = rn_mine;
+        for (int r = tid + kBlock; r < Nb; r += kBlock) rn_of[r] = row_norm[r];
+        if (grp == 0) {
+            float ss = frag_sumsq<T>(new_k);
+#pragma unroll
+            for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+            if (piece == 0) sh_newnorm = sqrtf(ss);
+        }
     }
     __syncthreads();
 
@@ -253,8 +338,8 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int j = j0 + u * kBlock;
-            rr[u] = j < Tn ? tok_row[j] : -1;
-            tn[u] = j < Tn ? tok_norm[j] : 0.f;
+            if (kPreload && j0 == tid) { rr[u] = pre_rr[u]; tn[u] = pre_tn[u]; }
+            else { rr[u] = j < Tn ? tok_row[j] : -1; tn[u] = j < Tn ? tok_norm[j] : 0.f; }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -275,8 +360,8 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int j = j0 + u * kBlock;
-            rr[u] = j < Tn ? tok_row[j] : -1;
-            tn[u] = j < Tn ? tok_norm[j] : 0.f;
+            if (kPreload && j0 == tid) { rr[u] = pre_rr[u]; tn[u] = pre_tn[u]; }
+            else { rr[u] = j < Tn ? tok_row[j] : -1; tn[u] = j < Tn ? tok_norm[j] : 0.f; }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -301,11 +386,14 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
         for (int u = 0; u < kUnroll; ++u) {
             const int j = j0 + u * kBlock;
             const bool ok = j < Tn;
-            rr[u] = ok ? tok_row[j] : -1;
-            tn[u] = ok ? tok_norm[j] : 0.f;
-            tg[u] = ok ? tok_glo[j] : 0.f;
-            tp[u] = ok ? tok_past[j] : 0.f;
-            tc[u] = ok ? tok_cur[j] : 0.f;
+            if (kPreload && j0 == tid) { rr[u] = pre_rr[u]; tn[u] = pre_tn[u]; tg[u] = pre_tg[u]; tp[u] = pre_tp[u]; tc[u] = pre_tc[u]; }
+            else {
+                rr[u] = ok ? tok_row[j] : -1;
+                tn[u] = ok ? tok_norm[j] : 0.f;
+                tg[u] = ok ? tok_glo[j] : 0.f;
+                tp[u] = ok ? tok_past[j] : 0.f;
+                tc[u] = ok ? tok_cur[j] : 0.f;
+            }
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
