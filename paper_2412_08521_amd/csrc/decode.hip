@@ -19,27 +19,6 @@ namespace ems {
 // ---- wave and block reductions.  Inside a wave the combine runs on DPP lane permutations
 // (xor 1, xor 2 inside quads, then the half-row and row mirrors), which have ALU latency;
 // the four row results are then read through scalar registers, so the result is uniform.
-template <int kCtrl>
-__device__ __forceinline__ float dpp_f(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, false));
-}
-template <int kCtrl>
-__device__ __forceinline__ int dpp_i(int v)
-{
-    return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, 0xf, false);
-}
-constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
-constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
-constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
-
-template <bool kMax> __device__ __forceinline__ float comb(float a, float b) { return kMax ? fmaxf(a, b) : a + b; }
-__device__ __forceinline__ float lane_value(float v, int lane)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
-}
-
 // all 16 lanes of every row end up with their row's result
 template <bool kMax>
 __device__ __forceinline__ float row_reduce(float v)

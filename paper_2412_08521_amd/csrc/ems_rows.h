@@ -61,4 +61,40 @@ template <> struct Pack<float> {
     }
 };
 
+// ---- DPP lane permutations (ALU latency, no LDS round trip)
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xf, 0xf, false));
+}
+template <int kCtrl>
+__device__ __forceinline__ int dpp_i(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, kCtrl, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i inside each group of 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i inside each row of 16
+
+template <bool kMax> __device__ __forceinline__ float comb(float a, float b) { return kMax ? fmaxf(a, b) : a + b; }
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+
+// Sum over the kLpr consecutive lanes that hold one row (kLpr = 8, 16 or 32); every lane of
+// the group gets the total.
+template <int kLpr>
+__device__ __forceinline__ float group_sum(float v)
+{
+    v += dpp_f<kDppXor1>(v);
+    v += dpp_f<kDppXor2>(v);
+    v += dpp_f<kDppHalfMirror>(v);
+    if constexpr (kLpr >= 16) v += dpp_f<kDppMirror>(v);
+    if constexpr (kLpr >= 32) v += __shfl_xor(v, 16);
+    return v;
+}
+
 }  // namespace ems

@@ -86,27 +86,49 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
     float best = -INFINITY;
     int arg = 0;
 
+    // Centre rows are gathered one stage ahead into registers (and their positions two stages
+    // ahead), so the global round trips run under the previous stage's MFMAs.
+    int pos_pf[kPerThread];
+    frag_t pf[kSrc][kPerThread];
+    auto load_pos = [&](int c0) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int ci = c0 + (threadIdx.x + i * kMrgBlock) / kCpr;
+            pos_pf[i] = ci < n_imp ? clamp_pos(imp[ci], N) : -1;
+        }
+    };
+    auto load_rows = [&]() {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int cc = (threadIdx.x + i * kMrgBlock) % kCpr;
+#pragma unroll
+            for (int s = 0; s < kSrc; ++s)
+                pf[s][i] = load_frag_or_zero(src[s], ((size_t)max(pos_pf[i], 0) * kCpr + cc) * 16, pos_pf[i] >= 0);
+        }
+    };
+    load_pos(0);
+    load_rows();
+    load_pos(kStageRows);
+
     for (int c0 = 0; c0 < n_imp; c0 += kStageRows) {
         __syncthreads();                                   // previous tile fully consumed
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const int c = threadIdx.x + i * kMrgBlock;
             const int row = c / kCpr, cc = c % kCpr;
-            const int ci = c0 + row;
-            const bool ok = ci < n_imp;
-            const int pos = ok ? clamp_pos(imp[ci], N) : 0;
 #pragma unroll
             for (int s = 0; s < kSrc; ++s) {
-                const frag_t v = load_frag_or_zero(src[s], ((size_t)pos * kCpr + cc) * 16, ok);
-                *reinterpret_cast<frag_t*>(lds[s] + row * kStride + cc * 16) = v;
+                *reinterpret_cast<frag_t*>(lds[s] + row * kStride + cc * 16) = pf[s][i];
                 // the kCpr consecutive lanes that hold one row add up its squares
-                float ss = frag_sumsq<T>(v);
-#pragma unroll
-                for (int o = kCpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+                const float ss = group_sum<kCpr>(frag_sumsq<T>(pf[s][i]));
                 if (cc == 0) lds_rn[s][row] = inv_norm(ss);
             }
         }
         __syncthreads();
+        if (c0 + kStageRows < n_imp) {                     // block-uniform
+            load_rows();
+            load_pos(c0 + 2 * kStageRows);
+        }
 #pragma unroll
         for (int rs = 0; rs < kStageRows / 32; ++rs) {
             const int cbase = c0 + rs * 32;
@@ -166,15 +188,15 @@ struct RowAcc {
         for (int i = 0; i < kE; ++i) { k[i] = 0.f; v[i] = 0.f; }
         wsum = 0.f;
     }
-    // adds token `pos` (unit key, raw value); returns the key's norm.  All kLpr lanes of
-    // the group must call together.
-    __device__ __forceinline__ float add(const T* K, const T* V, int pos, int piece)
+    static __device__ __forceinline__ frag_t load_piece(const T* X, int pos, int piece)
     {
-        const frag_t fk = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)pos * kLpr + piece) * 16);
-        const frag_t fv = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)pos * kLpr + piece) * 16);
-        float ss = frag_sumsq<T>(fk);
-#pragma unroll
-        for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        return *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(X) + ((size_t)pos * kLpr + piece) * 16);
+    }
+    // adds a token given its key and value pieces (unit key, raw value); returns the key's
+    // norm.  All kLpr lanes of the group must call together.
+    __device__ __forceinline__ float accumulate(const frag_t& fk, const frag_t& fv)
+    {
+        const float ss = group_sum<kLpr>(frag_sumsq<T>(fk));
         const float rn = inv_norm(ss);
         float xk[kE], xv[kE];
         Pack<T>::unpack(fk, xk);
@@ -184,13 +206,9 @@ struct RowAcc {
         return sqrtf(ss);
     }
     // the same with weight w >= 0 on the token (score-weighted merge, Sec. 4.2)
-    __device__ __forceinline__ float add_weighted(const T* K, const T* V, int pos, int piece, float w)
+    __device__ __forceinline__ float accumulate_weighted(const frag_t& fk, const frag_t& fv, float w)
     {
-        const frag_t fk = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)pos * kLpr + piece) * 16);
-        const frag_t fv = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)pos * kLpr + piece) * 16);
-        float ss = frag_sumsq<T>(fk);
-#pragma unroll
-        for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        const float ss = group_sum<kLpr>(frag_sumsq<T>(fk));
         const float rnw = inv_norm(ss) * w;
         float xk[kE], xv[kE];
         Pack<T>::unpack(fk, xk);
@@ -199,6 +217,14 @@ struct RowAcc {
         for (int i = 0; i < kE; ++i) { k[i] = __builtin_fmaf(xk[i], rnw, k[i]); v[i] = __builtin_fmaf(xv[i], w, v[i]); }
         wsum += w;
         return sqrtf(ss);
+    }
+    __device__ __forceinline__ float add(const T* K, const T* V, int pos, int piece)
+    {
+        return accumulate(load_piece(K, pos, piece), load_piece(V, pos, piece));
+    }
+    __device__ __forceinline__ float add_weighted(const T* K, const T* V, int pos, int piece, float w)
+    {
+        return accumulate_weighted(load_piece(K, pos, piece), load_piece(V, pos, piece), w);
     }
     // adds the groups together: afterwards every group holds the total
     template <bool kWeighted>
@@ -234,11 +260,25 @@ __device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const MergeArgs
         if (match) wlist[__popcll(mask & ((1ull << lane) - 1ull))] = clamp_pos(tbm[i], a.seq_len);
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        for (int m0 = 0; m0 < n; m0 += kGroups) {
-            const int m = m0 + grp;
-            if (m < n) {
-                if constexpr (kWeighted) acc.add_weighted(K, V, wlist[m], piece, fmaxf(Wt[wlist[m]], 0.f));
-                else acc.add(K, V, wlist[m], piece);
+        // kInFlight members per lane group at a time, all their loads issued before the first is
+        // added; a group still adds its members in ascending order
+        constexpr int kInFlight = 4;
+        for (int m0 = 0; m0 < n; m0 += kGroups * kInFlight) {
+            frag_t fk[kInFlight], fv[kInFlight];
+            float w[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int m = m0 + u * kGroups + grp;
+                const int pos = m < n ? wlist[m] : 0;
+                fk[u] = load_frag_or_zero(K, ((size_t)pos * kLpr + piece) * 16, m < n);
+                fv[u] = load_frag_or_zero(V, ((size_t)pos * kLpr + piece) * 16, m < n);
+                w[u] = (kWeighted && m < n) ? fmaxf(Wt[pos], 0.f) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                if (m0 + u * kGroups + grp >= n) break;
+                if constexpr (kWeighted) acc.accumulate_weighted(fk[u], fv[u], w[u]);
+                else acc.accumulate(fk[u], fv[u]);
             }
         }
         __builtin_amdgcn_wave_barrier();

@@ -167,25 +167,35 @@ __global__ __launch_bounds__(kRedBlock) void redundancy_kernel(StatsArgs a)
 
     float best = -INFINITY;
     const int c_end = min(N, t_block0 + kRedWaves * 32 - 1);  // earlier tokens the block can need
+    // the next stage's rows are fetched into registers under the current stage's MFMAs
+    frag_t pf[2][kPerThread];
+    auto load_rows = [&](int c0) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int c = threadIdx.x + i * kRedBlock;
+            const int ci = c0 + c / kCpr, cc = c % kCpr;
+            const bool ok = ci < c_end;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                pf[s][i] = load_frag_or_zero(src[s], ((size_t)(ok ? ci : 0) * kCpr + cc) * 16, ok);
+        }
+    };
+    load_rows(0);
     for (int c0 = 0; c0 < c_end; c0 += kStageRows) {
         __syncthreads();                                   // previous tile fully consumed
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const int c = threadIdx.x + i * kRedBlock;
             const int row = c / kCpr, cc = c % kCpr;
-            const int ci = c0 + row;
-            const bool ok = ci < c_end;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const frag_t v = load_frag_or_zero(src[s], ((size_t)(ok ? ci : 0) * kCpr + cc) * 16, ok);
-                *reinterpret_cast<frag_t*>(lds[s] + row * kStride + cc * 16) = v;
-                float ss = frag_sumsq<T>(v);
-#pragma unroll
-                for (int o = kCpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+                *reinterpret_cast<frag_t*>(lds[s] + row * kStride + cc * 16) = pf[s][i];
+                const float ss = group_sum<kCpr>(frag_sumsq<T>(pf[s][i]));
                 if (cc == 0) lds_rn[s][row] = inv_norm(ss);
             }
         }
         __syncthreads();
+        if (c0 + kStageRows < c_end) load_rows(c0 + kStageRows);   // block-uniform
 #pragma unroll
         for (int rs = 0; rs < kStageRows / 32; ++rs) {
             const int cbase = c0 + rs * 32;
