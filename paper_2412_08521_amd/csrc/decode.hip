@@ -3,13 +3,14 @@
 //
 // decode_init_kernel  builds the per-token table (position, cache row, key norm, s_Glo,
 //                     s_Loc^past, s_Loc^cur) from what the prefill compression returned.
-// decode_step_kernel  one generated token: one 1024-thread block per (batch, kv-head) runs
-//                     the whole step -- attention row of the new query over the expanded
-//                     run-time cache (one dot product per cache ROW, shared by the tokens
-//                     that share the entry), score accumulation, window ring shift, least
-//                     important centre, its most similar centre, merge-or-evict with the
-//                     look-up-table remap, new centre, past/cur swap.  Phases are separated
-//                     by block barriers that every thread reaches.
+// decode_step_kernel  one generated token: one block per (batch, kv-head) runs the whole
+//                     step -- attention row of the new query over the expanded run-time
+//                     cache (one dot product per cache ROW, shared by the tokens that share
+//                     the entry; coalesced row loads, v_dot2 partials added with DPP),
+//                     score accumulation, window ring shift, least important centre, its
+//                     most similar centre, merge-or-evict with the look-up-table remap, new
+//                     centre, past/cur swap.  Phases are separated by block barriers that
+//                     every thread reaches.
 #include "ems_common.h"
 #include "ems_kernels.h"
 #include "ems_rows.h"
@@ -114,6 +115,19 @@ __device__ __forceinline__ void block_arg(float& v, int& i, float* fbuf, int* ib
         for (int w = 1; w < kWaves; ++w)
             if (better<kMin>(fbuf[w], ibuf[w], v, i)) { v = fbuf[w]; i = ibuf[w]; }
     }
+}
+
+// dot product of the 8 bf16 elements of two 16-byte row pieces, f32 accumulation
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot8_bf16(const frag_t& x, const frag_t& y)
+{
+    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, x), b = __builtin_bit_cast(bf16x8_t, y);
+    float acc = 0.f;
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), acc, false);
+    return acc;
 }
 
 // register `idx` (0..15) of a 32x32 accumulator, idx not known at compile time
@@ -229,19 +243,83 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     const char* kn = reinterpret_cast<const char*>(a.k_new) + (size_t)bkv * D * sizeof(T);
     const char* vn = reinterpret_cast<const char*>(a.v_new) + (size_t)bkv * D * sizeof(T);
 
-    // ---- phase 1: q_g . (every cache row) as an MFMA contraction ------------------------
-    // A operand: 32 cache rows per tile (row index Nb stands for the new token's own key);
-    // B operand: the group's q-heads in columns 0..G-1, zeros elsewhere.  Lane (col = g,
-    // half) of the accumulator then holds the dots of q_g with 16 of the tile's rows.
+    // ---- phase 1: q_g . (every cache row), the new token's own key included as row Nb ----
+    // bf16: a row is kLpr consecutive lanes x 16 bytes, so a wave-wide load covers 64 / kLpr
+    // whole rows (fully coalesced); each lane forms the partial dots of its 8 elements with
+    // v_dot2 and the kLpr partials are added with DPP.  One dot per cache ROW serves every
+    // token that shares the entry.
+    // f32 (validation mode): MFMA contraction, 32 cache rows per tile as the A operand, the
+    // group's q-heads in B columns 0..G-1.
     // Everything this thread will need from global memory that does not depend on earlier
-    // phases is requested here, behind the first tile's loads, so that the round trips overlap:
+    // phases is requested here, behind the first row loads, so that the round trips overlap:
     // the first batch of table elements (all of them for small tables), the centre token of
     // "its" entry, its share of the row norms, the new token's row.
+    constexpr bool kDot2 = sizeof(T) == 2;
+    constexpr int kRowsPerWave = kWave / kLpr;               // whole rows per wave-wide load
+    constexpr int kRowsPerPass = kWaves * kRowsPerWave;
+    constexpr int kInFlight = kBlock == 1024 ? 8 : 4;        // row loads in flight per lane (bf16 path)
+    const int sub = lane / kLpr;                             // this lane's row within the wave's load
     const int ct_mine = tid < n_imp ? entry_tok[tid] : 0;    // used in phase 4
     frag_t new_k = zero_frag(), new_v = zero_frag();
     int pre_rr[kUnroll];
     float pre_tn[kUnroll], pre_tg[kUnroll], pre_tp[kUnroll], pre_tc[kUnroll];
-    {
+    auto preload_table = [&]() {
+#pragma unroll
+        for (int u = 0; u < (kPreload ? kUnroll : 0); ++u) {
+            const int j = tid + u * kBlock;
+            const bool ok = j < Tn;
+            pre_rr[u] = ok ? tok_row[j] : -1;
+            pre_tn[u] = ok ? tok_norm[j] : 0.f;
+            pre_tg[u] = ok ? tok_glo[j] : 0.f;
+            pre_tp[u] = ok ? tok_past[j] : 0.f;
+            pre_tc[u] = ok ? tok_cur[j] : 0.f;
+        }
+    };
+    if constexpr (kDot2) {
+        frag_t qp[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) qp[g] = *reinterpret_cast<const frag_t*>(qn + ((size_t)g * kLpr + piece) * 16);
+        new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
+        frag_t fk[kInFlight];
+        auto load_rows = [&](int r0) {
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int r = r0 + u * kRowsPerPass;
+                fk[u] = r < Nb ? *reinterpret_cast<const frag_t*>(Kc + ((size_t)r * kLpr + piece) * 16) : new_k;
+            }
+        };
+        const int r_first = wave * kRowsPerWave + sub;
+        load_rows(r_first);
+        preload_table();
+        const float rn_mine = tid < Nb ? row_norm[tid] : 0.f;
+        if (grp == 0) new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
+        for (int r0 = r_first; r0 <= Nb; r0 += kRowsPerPass * kInFlight) {
+            if (r0 != r_first) load_rows(r0);
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int r = r0 + u * kRowsPerPass;
+                if (r > Nb) break;                           // uniform over the row's lanes
+                float d[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) d[g] = group_sum<kLpr>(dot8_bf16(fk[u], qp[g]));
+                if (piece == 0) {
+                    if (r < Nb) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) dot[(size_t)g * Nb + r] = d[g];
+                    } else {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) sh_self[g] = a.scale_log2e * d[g];
+                    }
+                }
+            }
+        }
+        if (tid < Nb) rn_of[tid] = rn_mine;
+        for (int r = tid + kBlock; r < Nb; r += kBlock) rn_of[r] = row_norm[r];
+        if (grp == 0) {
+            const float ss = group_sum<kLpr>(frag_sumsq<T>(new_k));
+            if (piece == 0) sh_newnorm = sqrtf(ss);
+        }
+    } else {
         frag_t bq[kFrags];
 #pragma unroll
         for (int f = 0; f < kFrags; ++f)
@@ -258,17 +336,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
             }
         };
         load_tiles(wave);
-        // (behind the first tiles in the memory queue)
-#pragma unroll
-        for (int u = 0; u < (kPreload ? kUnroll : 0); ++u) {
-            const int j = tid + u * kBlock;
-            const bool ok = j < Tn;
-            pre_rr[u] = ok ? tok_row[j] : -1;
-            pre_tn[u] = ok ? tok_norm[j] : 0.f;
-            pre_tg[u] = ok ? tok_glo[j] : 0.f;
-            pre_tp[u] = ok ? tok_past[j] : 0.f;
-            pre_tc[u] = ok ? tok_cur[j] : 0.f;
-        }
+        preload_table();
         const float rn_mine = tid < Nb ? row_norm[tid] : 0.f;
         if (grp == 0) {
             new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
@@ -297,9 +365,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
         if (tid < Nb) rn_of[tid] = rn_mine;
         for (int r = tid + kBlock; r < Nb; r += kBlock) rn_of[r] = row_norm[r];
         if (grp == 0) {
-            float ss = frag_sumsq<T>(new_k);
-#pragma unroll
-            for (int o = kLpr / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+            const float ss = group_sum<kLpr>(frag_sumsq<T>(new_k));
             if (piece == 0) sh_newnorm = sqrtf(ss);
         }
     }
@@ -442,10 +508,34 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     const int f = entry_tok[s_star];
 
     // ---- phase 5: its most similar other centre (Eq. 5, cosine of the stored keys) -----
-    // Two MFMA chains per tile of 32 entries: tile x (row s_star in every column) gives the
-    // dot products, tile x tile gives the squared norms on its diagonal.
+    // bf16: per entry row the dot with the chosen row and the row's own squared norm, again as
+    // v_dot2 partials added with DPP.  f32: two MFMA chains per tile of 32 entries -- tile x
+    // (chosen row in every column) for the dots, tile x tile for the squared norms on its
+    // diagonal.
     float cv = 0.f;
     int ci = -1;
+    if constexpr (kDot2) {
+        const frag_t sp = *reinterpret_cast<const frag_t*>(Kc + ((size_t)s_star * kLpr + piece) * 16);
+        const float rn_star = inv_norm(group_sum<kLpr>(dot8_bf16(sp, sp)));
+        const int s_first = wave * kRowsPerWave + sub;
+        for (int s0 = s_first; s0 < n_imp; s0 += kRowsPerPass * kInFlight) {
+            frag_t fk[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int s = s0 + u * kRowsPerPass;
+                fk[u] = load_frag_or_zero(Kc, ((size_t)s * kLpr + piece) * 16, s < n_imp);
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int s = s0 + u * kRowsPerPass;
+                if (s >= n_imp) break;                       // uniform over the row's lanes
+                const float d = group_sum<kLpr>(dot8_bf16(fk[u], sp));
+                const float e2 = group_sum<kLpr>(dot8_bf16(fk[u], fk[u]));
+                const float sim = (d * inv_norm(e2)) * rn_star;
+                if (piece == 0 && s != s_star && better<false>(sim, s, cv, ci)) { cv = sim; ci = s; }
+            }
+        }
+    } else
     {
         frag_t bs[kFrags];
         float ss = 0.f;
