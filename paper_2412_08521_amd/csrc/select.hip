@@ -399,6 +399,8 @@ __global__ __launch_bounds__(kSelBlock) void select_reg_kernel(SelectArgs a)
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const bool cand = base + i * kWave < Nc;
+        // almost every (wave, item) slice lies entirely below the second cut: nothing to rank
+        if (__ballot(cand && key[i] >= T2) == 0ull) continue;         // wave-uniform
         const unsigned long long m1 = __ballot(cand && key[i] == T1), m2 = __ballot(cand && key[i] == T2);
         int rank;
         if (key[i] == T1) rank = G1 + r1 + below_count(m1);
@@ -419,6 +421,7 @@ __global__ __launch_bounds__(kSelBlock) void select_reg_kernel(SelectArgs a)
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const bool ii = (imp_mask >> i) & 1u, tt = (tbm_mask >> i) & 1u;
+        if (__ballot(ii || tt) == 0ull) continue;                        // wave-uniform
         const unsigned long long mi = __ballot(ii), mt = __ballot(tt);
         if (ii) { const int at = bi + below_count(mi); if (at < a.n_imp) imp[at] = base + i * kWave; }
         if (tt && tbm) { const int at = bt + below_count(mt); if (at < a.n_tbm) tbm[at] = base + i * kWave; }
