@@ -47,29 +47,6 @@ __device__ __forceinline__ void hist_add(int* hist, int digit, bool on)
     if (on && digit != d0) atomicAdd(&hist[digit], 1);
 }
 
-// Exclusive prefix sums over the block (thread order) of two integers; also the totals.
-__device__ __forceinline__ void block_scan2(int a, int b, int& ea, int& eb, int& ta, int& tb,
-                                            int (*sm)[2])
-{
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    int ia = a, ib = b;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const int ua = __shfl_up(ia, o), ub = __shfl_up(ib, o);
-        if (lane >= o) { ia += ua; ib += ub; }
-    }
-    __syncthreads();
-    if (lane == kWave - 1) { sm[wave][0] = ia; sm[wave][1] = ib; }
-    __syncthreads();
-    int wa = 0, wb = 0, sa = 0, sb = 0;
-    for (int w = 0; w < kSelWaves; ++w) {
-        const int xa = sm[w][0], xb = sm[w][1];
-        if (w < wave) { wa += xa; wb += xb; }
-        sa += xa; sb += xb;
-    }
-    ea = wa + ia - a; eb = wb + ib - b; ta = sa; tb = sb;
-}
-
 __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
 {
     __shared__ float red[kSelWaves][2];
