@@ -109,7 +109,7 @@ bool ws_ok(const void* ws, size_t have, size_t need)
 
 extern "C" {
 
-int ems_version(void) { return 100; }
+int ems_version(void) { return 200; }
 
 const char* ems_strerror(int status)
 {
