@@ -678,10 +678,14 @@ static hipError_t launch_decode_step_b(const DecodeStepArgs& a, hipStream_t st)
 template <typename T, int D>
 static hipError_t launch_decode_step_t(const DecodeStepArgs& a, hipStream_t st)
 {
-    const int Tn = a.n_imp + a.n_tbm + a.window;
     // f32 rows need twice the operand registers: the validation mode always takes the small block
-    if (sizeof(T) == 4 || (a.budget <= 512 && Tn <= 2048)) return launch_decode_step_b<T, D, 256>(a, st);
-    return launch_decode_step_b<T, D, 1024>(a, st);
+    if constexpr (sizeof(T) == 4) {
+        return launch_decode_step_b<T, D, 256>(a, st);
+    } else {
+        const int Tn = a.n_imp + a.n_tbm + a.window;
+        if (a.budget <= 512 && Tn <= 2048) return launch_decode_step_b<T, D, 256>(a, st);
+        return launch_decode_step_b<T, D, 1024>(a, st);
+    }
 }
 
 hipError_t launch_decode_step(const DecodeStepArgs& a, bool f32, hipStream_t st)
