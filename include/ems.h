@@ -262,6 +262,8 @@ int ems_redundancy_rate(const ems_params* p, const void* k, const void* v,
  *   tok_pos     [B, Hkv, T] i32  position, -1 = free element
  *   tok_row     [B, Hkv, T] i32  cache row the token lives in, -1 = free element
  *   tok_norm, tok_glo, tok_past, tok_cur [B, Hkv, T] f32
+ *   step_count  [1] i32  tokens generated so far (0 after ems_decode_init); lets a step be enqueued
+ *                        without a host-side counter, e.g. from a captured HIP graph
  * A token's run-time key is (tok_norm / row_norm[row]) * k_cache[row], its value v_cache[row].
  */
 typedef struct {
@@ -276,7 +278,11 @@ typedef struct {
     float* tok_glo;
     float* tok_past;
     float* tok_cur;
+    int32_t* step_count;
 } ems_decode_state;
+
+/* Value of `step` that makes ems_decode_step read the counter in the state instead. */
+#define EMS_STEP_FROM_STATE (-1)
 
 /* Bytes of device scratch ems_decode_step needs (host only). */
 int ems_decode_workspace_bytes(const ems_params* p, size_t* decode_ws);
@@ -297,8 +303,10 @@ int ems_decode_init(const ems_params* p, const float* s_glo, const float* s_loc,
 
 /*
  * One generated token (Sec. 3.2, decoding paragraph; App. A "Evict-then-Merge Details"),
- * for all heads in one launch.  `step` = number of tokens generated before this one; the new
- * token's position is seq_len + step.  In order, per kv-head:
+ * for all heads in one launch.  `step` = number of tokens generated before this one, or
+ * EMS_STEP_FROM_STATE to take it from state->step_count (a device scalar, so that the same
+ * recorded launch can be replayed for token after token); either way step_count is left at
+ * step + 1.  The new token's position is seq_len + step.  In order, per kv-head:
  *   1. attention row of the new queries (q-heads of the group, Eq. 1) over the run-time
  *      cache -- every live table element expanded, the window tokens, the new token itself;
  *   2. s_Glo and s_Loc^cur of every live token += the row (summed over the group);

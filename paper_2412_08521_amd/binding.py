@@ -25,6 +25,7 @@ EMS_F32 = 1
 EMS_SIM_KEY = 0
 EMS_SIM_VALUE = 1
 EMS_SIM_KEY_VALUE = 2
+EMS_STEP_FROM_STATE = -1
 
 EXPORTS = ("ems_version", "ems_strerror", "ems_partition_sizes", "ems_workspace_bytes",
            "ems_global_local_score", "ems_attention_lse", "ems_global_local_score_from_lse",
@@ -41,7 +42,7 @@ class ems_params(C.Structure):
 
 
 STATE_FIELDS = ("k_cache", "v_cache", "row_norm", "entry_count", "entry_tok", "tok_pos", "tok_row",
-                "tok_norm", "tok_glo", "tok_past", "tok_cur")
+                "tok_norm", "tok_glo", "tok_past", "tok_cur", "step_count")
 
 
 class ems_decode_state(C.Structure):
@@ -364,7 +365,7 @@ class DecodeState:
                   ("entry_tok", (B, H, n_imp), torch.int32), ("tok_pos", (B, H, T), torch.int32),
                   ("tok_row", (B, H, T), torch.int32), ("tok_norm", (B, H, T), torch.float32),
                   ("tok_glo", (B, H, T), torch.float32), ("tok_past", (B, H, T), torch.float32),
-                  ("tok_cur", (B, H, T), torch.float32)]
+                  ("tok_cur", (B, H, T), torch.float32), ("step_count", (1,), torch.int32)]
         sizes = [(4 * int(torch.Size(shape).numel()) + 255) // 256 * 256 for _, shape, _ in shapes]
         self.slab = torch.zeros(sum(sizes), dtype=torch.uint8, device=dev)
         off = 0

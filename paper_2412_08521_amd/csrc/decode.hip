@@ -184,6 +184,7 @@ __global__ __launch_bounds__(256) void decode_init_kernel(DecodeInitArgs a)
     a.st.tok_glo[o] = live ? a.s_glo[(size_t)bkv * N + cp] : 0.f;
     a.st.tok_past[o] = live ? a.s_loc[(size_t)bkv * N + cp] : 0.f;
     a.st.tok_cur[o] = 0.f;
+    if (bkv == 0 && j == 0) *a.st.step_count = 0;
 }
 
 // ------------------------------------------------------------------------------------
@@ -220,6 +221,9 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     const int Tn = E + W;
     const int bkv = blockIdx.x;
     const int tid = threadIdx.x;
+    // tokens generated before this one: the caller's count, or the counter kept in the state
+    // (which is advanced by a separate launch after this kernel, so every block reads the same)
+    const int step = a.step >= 0 ? a.step : *a.st.step_count;
     const int lane = tid % kWave, wave = tid / kWave;
     const int col = lane & 31, half = lane >> 5;             // MFMA operand row / k-half of this lane
     const int grp = tid / kLpr, piece = tid % kLpr;
@@ -478,7 +482,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     block_reduce<kWaves, 2, false>(tot2, vbuf);              // also: every token's scalars are written
 
     // ---- phase 3: the oldest window token leaves, the new token takes its ring slot ----
-    const int ring = a.step % W;
+    const int ring = step % W;
     const int jo = E + ring, ro = n_imp + ring;
     if (grp == 0) {
         old_k[piece] = *reinterpret_cast<const frag_t*>(Kc + ((size_t)ro * kLpr + piece) * 16);
@@ -489,7 +493,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     if (tid == 0) {
         old_pos = tok_pos[jo];
         old_sc[0] = tok_norm[jo]; old_sc[1] = tok_glo[jo]; old_sc[2] = tok_past[jo]; old_sc[3] = tok_cur[jo];
-        tok_pos[jo] = a.pos_new; tok_row[jo] = ro; tok_norm[jo] = sh_newnorm;
+        tok_pos[jo] = a.seq_len + step; tok_row[jo] = ro; tok_norm[jo] = sh_newnorm;
         tok_glo[jo] = self_tot; tok_past[jo] = 0.f; tok_cur[jo] = self_tot;
         row_norm[ro] = sh_newnorm;
     }
@@ -640,9 +644,14 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     __syncthreads();
 
     // ---- phase 7: a full window of queries: s_Loc^cur becomes s_Loc^past (Sec. 3.2) ----
-    if ((a.step + 1) % W == 0) {
+    if ((step + 1) % W == 0) {
         for (int j = tid; j < Tn; j += kBlock) { tok_past[j] = tok_cur[j]; tok_cur[j] = 0.f; }
     }
+}
+
+__global__ void decode_bump_kernel(int32_t* step_count, int step)
+{
+    *step_count = (step >= 0 ? step : *step_count) + 1;
 }
 
 // ------------------------------------------------------------------------------------
@@ -672,6 +681,9 @@ static hipError_t launch_decode_step_b(const DecodeStepArgs& a, hipStream_t st)
         case 8: hipLaunchKernelGGL((decode_step_kernel<T, D, 8, kBlock>), g, b, lds, st, a); break;
         default: return hipErrorInvalidValue;
     }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(decode_bump_kernel, dim3(1), dim3(1), 0, st, a.st.step_count, a.step);
     return hipGetLastError();
 }
 

@@ -340,7 +340,7 @@ static size_t decode_ws_bytes(const ems_params* p)
 static bool state_ok(const ems_decode_state* s)
 {
     return s && s->k_cache && s->v_cache && s->row_norm && s->entry_count && s->entry_tok && s->tok_pos &&
-           s->tok_row && s->tok_norm && s->tok_glo && s->tok_past && s->tok_cur;
+           s->tok_row && s->tok_norm && s->tok_glo && s->tok_past && s->tok_cur && s->step_count;
 }
 
 static ems::DecodeState to_internal(const ems_decode_state* s)
@@ -349,7 +349,7 @@ static ems::DecodeState to_internal(const ems_decode_state* s)
     d.k_cache = s->k_cache; d.v_cache = s->v_cache; d.row_norm = s->row_norm;
     d.entry_count = s->entry_count; d.entry_tok = s->entry_tok; d.tok_pos = s->tok_pos;
     d.tok_row = s->tok_row; d.tok_norm = s->tok_norm; d.tok_glo = s->tok_glo;
-    d.tok_past = s->tok_past; d.tok_cur = s->tok_cur;
+    d.tok_past = s->tok_past; d.tok_cur = s->tok_cur; d.step_count = s->step_count;
     return d;
 }
 
@@ -392,7 +392,7 @@ int ems_decode_step(const ems_params* p, const ems_decode_state* state, int32_t 
     int n_imp, n_tbm;
     partition_sizes(p, &n_imp, &n_tbm);
     if (!state_ok(state) || !q_new || !k_new || !v_new) return EMS_ERR_INVALID_ARG;
-    if (step < 0 || (long long)p->seq_len + step > 0x7fffffffll) return EMS_ERR_INVALID_ARG;
+    if (step < EMS_STEP_FROM_STATE || (long long)p->seq_len + step > 0x7fffffffll) return EMS_ERR_INVALID_ARG;
     if (!ws_ok(ws, ws_bytes, decode_ws_bytes(p))) return EMS_ERR_WORKSPACE;
     const size_t bkv = (size_t)p->batch * p->kv_heads;
     const int g = p->q_heads / p->kv_heads;
@@ -406,7 +406,7 @@ int ems_decode_step(const ems_params* p, const ems_decode_state* state, int32_t 
     const size_t stage_floats = (size_t)(g + 1) * p->budget;
     a.lds_floats = stage_floats * sizeof(float) <= 60 * 1024 ? (int)stage_floats : 0;
     a.bkv = (int)bkv; a.group = g; a.head_dim = p->head_dim; a.window = p->window; a.budget = p->budget;
-    a.n_imp = n_imp; a.n_tbm = n_tbm; a.step = step; a.pos_new = p->seq_len + step;
+    a.n_imp = n_imp; a.n_tbm = n_tbm; a.step = step; a.seq_len = p->seq_len;
     a.tau = p->tau;
     const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
     a.scale_log2e = (float)(scale * 1.4426950408889634074);

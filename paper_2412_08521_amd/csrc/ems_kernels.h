@@ -79,6 +79,7 @@ struct DecodeState {
     float* tok_glo;
     float* tok_past;
     float* tok_cur;
+    int32_t* step_count;    // [1]
 };
 
 struct DecodeInitArgs {
@@ -103,7 +104,8 @@ struct DecodeStepArgs {
     float* sim_opt;         // [bkv] or null
     float* ws;              // [bkv, (group + 1) * budget] staging when it does not fit in LDS
     int lds_floats;         // (group + 1) * budget when staged in LDS, else 0
-    int bkv, group, head_dim, window, budget, n_imp, n_tbm, step, pos_new;
+    int bkv, group, head_dim, seq_len, window, budget, n_imp, n_tbm;
+    int step;               // >= 0, or -1: read st.step_count
     float tau, scale_log2e;
 };
 

@@ -119,14 +119,14 @@ def test_decode_argument_errors(lib):
     cp = p.c()
     d = C.c_void_p(256)
     st = B.ems_decode_state(*[256] * len(B.STATE_FIELDS))
-    assert C.sizeof(B.ems_decode_state) == 11 * C.sizeof(C.c_void_p)
+    assert C.sizeof(B.ems_decode_state) == 12 * C.sizeof(C.c_void_p)
     need = B.ems_decode_workspace_bytes(p)
     assert need >= 4 * (2 * 2 * 64 + 2 * 48) and need % 256 == 0
     # null state member, null token, negative step, workspace too small
-    hole = B.ems_decode_state(*([256] * 5 + [0] + [256] * 5))
+    hole = B.ems_decode_state(*([256] * 5 + [0] + [256] * 6))
     assert lib.ems_decode_step(C.byref(cp), C.byref(hole), 0, d, d, d, None, None, None, d, need, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_decode_step(C.byref(cp), C.byref(st), 0, None, d, d, None, None, None, d, need, None) == B.EMS_ERR_INVALID_ARG
-    assert lib.ems_decode_step(C.byref(cp), C.byref(st), -1, d, d, d, None, None, None, d, need, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_decode_step(C.byref(cp), C.byref(st), -2, d, d, d, None, None, None, d, need, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_decode_step(C.byref(cp), C.byref(st), 0, d, d, d, None, None, None, d, need - 1, None) == B.EMS_ERR_WORKSPACE
     assert lib.ems_decode_step(C.byref(cp), C.byref(st), 0, d, d, d, None, None, None, C.c_void_p(8), need, None) == B.EMS_ERR_WORKSPACE
     assert lib.ems_decode_init(C.byref(cp), d, d, d, d, d, d, d, None, None) == B.EMS_ERR_INVALID_ARG

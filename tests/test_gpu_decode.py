@@ -50,6 +50,8 @@ def _prefill(shape, mode, tau, seed):
 def _host_state(st, b, h):
     out = {}
     for name in B.STATE_FIELDS:
+        if name == "step_count":
+            continue
         a = _np(getattr(st, name)[b, h])
         out[name] = a.astype(np.int64) if a.dtype.kind == "i" else a.astype(np.float64)
     return out
