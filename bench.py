@@ -249,6 +249,14 @@ def time_extras(args, p, w, B, torch, timed, k, v, s_glo, s_loc, imp, tbm, merge
         for _ in range(4):
             one()
         out["decode_step"] = timed(one, n) * 1e3
+        # the same step recorded once (step counter read from the state) and replayed from a HIP graph
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                B.ems_decode_step(p, state[0], B.EMS_STEP_FROM_STATE, qn[0], kn[0], vn[0], ws=ws, out=res)
+        torch.cuda.synchronize()
+        out["decode_step_graph_replay"] = timed(graph.replay, n) * 1e3
         e = 4 if args.f32 else 2
         per_head = (w.budget + n_imp) * w.head_dim * e + n_exp * 40
         out["decode_step_algorithmic_bytes"] = per_head * w.batch * w.kv_heads
