@@ -149,3 +149,31 @@ def test_stats_argument_errors(lib):
     assert lib.ems_redundancy_rate(C.byref(cp), None, d, d, d, None) == B.EMS_ERR_INVALID_ARG
     odd = _bad(head_dim=96).c()
     assert lib.ems_redundancy_rate(C.byref(odd), d, d, d, d, None) == B.EMS_ERR_UNSUPPORTED
+
+
+def test_header_is_plain_c_and_links(lib, tmp_path):
+    """include/ems.h compiles as C99 and a C program can call the host-only entry points."""
+    import subprocess
+    src = tmp_path / "use_ems.c"
+    src.write_text(r'''
+#include "ems.h"
+#include <stdio.h>
+int main(void) {
+    ems_params p = {1, 8, 2, 128, 4096, 32, 256, 0.5f, 0.6f, 7, 0.0f, EMS_BF16};
+    int32_t n_imp = 0, n_tbm = 0;
+    size_t a = 0, b = 0, c = 0, d = 0;
+    if (ems_partition_sizes(&p, &n_imp, &n_tbm) != EMS_OK) return 1;
+    if (ems_workspace_bytes(&p, &a, &b, &c) != EMS_OK) return 2;
+    if (ems_decode_workspace_bytes(&p, &d) != EMS_OK) return 3;
+    if (ems_global_local_score(&p, 0, 0, 0, 0, 0, 0, 0, 0) != EMS_ERR_INVALID_ARG) return 4;
+    printf("%d %d %d %zu %zu %zu %zu %s\n", ems_version(), (int)n_imp, (int)n_tbm, a, b, c, d, ems_strerror(EMS_ERR_WORKSPACE));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_ems"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe), "-L", libdir, "-lems_hip", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) >= 200 and (int(out[1]), int(out[2])) == (224, 128)
+    assert all(int(x) % 256 == 0 for x in out[3:7]) and "workspace" in " ".join(out[7:])
