@@ -160,6 +160,24 @@ def main():
              "unit": "TFLOP/s", "frac": round(flops_pass / (ms_pass1 * 1e-3) / 1e12 / peak, 4),
              "ms_per_launch": round(ms_pass1, 4)}
 
+    # ---- the machine's own ceilings in the same process: a loop of independent bf16 MFMAs
+    # (16 waves per compute unit) and a plain 16-byte vector copy of Q
+    sink = torch.empty(1024 * 256, dtype=torch.float32, device="cuda")
+    B.ems_probe_mfma(1024, 2000, sink)
+    torch.cuda.synchronize()
+    probe_flops = 1024 * 4 * 20000 * 4 * 32768
+    ms_mfma = timed(lambda: B.ems_probe_mfma(1024, 20000, sink), 3)
+    q_copy = torch.empty_like(q)
+    B.ems_probe_copy(q, q_copy)
+    ms_copy = timed(lambda: B.ems_probe_copy(q, q_copy), 5)
+    copy_bytes = 2 * q.numel() * q.element_size()
+    del q_copy
+    ceilings = {"mfma_bf16_tflops": round(probe_flops / (ms_mfma * 1e-3) / 1e12, 1),
+                "copy_gbps": round(copy_bytes / (ms_copy * 1e-3) / 1e9, 1)}
+    log(f"measured ceilings: {ceilings}")
+    if not args.f32:
+        roofline["frac_of_measured_ceiling"] = round(achieved / ceilings["mfma_bf16_tflops"], 4)
+
     tokens = w.batch * w.seq_len
     result = {
         "metric": "compressed tokens/s per layer (score+evict+merge)",
@@ -172,7 +190,7 @@ def main():
                    "window": w.window, "budget": w.budget, "merge_ratio": w.merge_ratio,
                    "tau": args.tau, "pool_kernel": w.pool_kernel, "layer": args.layer},
         "stages_us": {k_: round(v_ * 1e3, 1) for k_, v_ in stages.items()},
-        "roofline": roofline, "score_pass1": pass1,
+        "roofline": roofline, "score_pass1": pass1, "ceilings": ceilings,
     }
 
     # ---- entry points outside the headline step, same shapes, reported on their own

@@ -13,8 +13,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 OBJ_DIR = os.path.join(_HERE, "_build")
 LIB = os.path.join(_HERE, "libems_hip.so")
-SOURCES = ["ems_api.hip", "score.hip", "select.hip", "merge.hip", "decode.hip", "stats.hip"]
-HEADERS = ["ems_common.h", "ems_kernels.h", "ems_rows.h", os.path.join("..", "..", "include", "ems.h")]
+SOURCES = ["ems_api.hip", "score.hip", "select.hip", "merge.hip", "decode.hip", "stats.hip", "probe.hip"]
+HEADERS = ["ems_common.h", "ems_kernels.h", "ems_rows.h", os.path.join("..", "..", "include", "ems.h"),
+           os.path.join("..", "..", "include", "ems_probe.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -20,7 +20,7 @@ def lib():
 
 
 def test_exports_match_header(lib):
-    text = open(os.path.join(ROOT, "include", "ems.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(ems_[a-z_]+)\s*\(", text))
     assert declared == set(B.EXPORTS)
@@ -177,3 +177,13 @@ int main(void) {
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
     assert int(out[0]) >= 200 and (int(out[1]), int(out[2])) == (224, 128)
     assert all(int(x) % 256 == 0 for x in out[3:7]) and "workspace" in " ".join(out[7:])
+
+
+def test_probe_argument_errors(lib):
+    d = C.c_void_p(256)
+    assert lib.ems_probe_mfma(0, 10, d, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_probe_mfma(8, 0, d, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_probe_mfma(8, 10, None, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_probe_copy(d, d, 24, None) == B.EMS_ERR_INVALID_ARG      # not a multiple of 16
+    assert lib.ems_probe_copy(C.c_void_p(8), d, 32, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_probe_copy(None, d, 32, None) == B.EMS_ERR_INVALID_ARG

@@ -507,3 +507,14 @@ def test_zero_keys_identical_keys_and_full_budget(mode):
     o2 = B.ems_evict_merge(p2, kd, vd, imp2, tbm2)
     assert torch.equal(o2["k_out"][:, :, :n], kd) and torch.equal(o2["v_out"][:, :, :n], vd)
     assert (o2["slot_count"][..., :-1] == 1).all() and (o2["slot_count"][..., -1] == 0).all()
+
+
+def test_probe_kernels_run():
+    """The measurement kernels: the copy copies, the MFMA loop leaves finite values."""
+    src = torch.randn(1 << 20, device="cuda")
+    dst = torch.zeros_like(src)
+    assert B.ems_probe_copy(src, dst) == 2 * src.numel() * 4
+    sink = torch.empty(8 * 256, dtype=torch.float32, device="cuda")
+    assert B.ems_probe_mfma(8, 10, sink) == 8 * 4 * 10 * 4 * 32768
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst) and torch.isfinite(sink).all()
