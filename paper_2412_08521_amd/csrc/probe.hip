@@ -28,8 +28,14 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* sink, int iters)
 
 __global__ __launch_bounds__(256) void probe_copy_kernel(const frag_t* src, frag_t* dst, size_t n16)
 {
+    // four 16-byte loads in flight per thread, each a fully coalesced wave-wide access
     const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const frag_t a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 }  // namespace ems
