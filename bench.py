@@ -191,6 +191,11 @@ def main():
                    "tau": args.tau, "pool_kernel": w.pool_kernel, "layer": args.layer},
         "stages_us": {k_: round(v_ * 1e3, 1) for k_, v_ in stages.items()},
         "roofline": roofline, "score_pass1": pass1, "ceilings": ceilings,
+        # context, not the headline: what the step costs when the caller's attention kernel
+        # hands over the row log-sum-exp and only the second pass runs (the paper's own design)
+        "with_caller_lse": {"ms_per_step": round(ms_pass2 + stages["select"] + stages["evict_merge"], 4),
+                            "value": round(tokens / ((ms_pass2 + stages["select"] + stages["evict_merge"]) * 1e-3), 1),
+                            "unit": "tokens/s"},
     }
 
     # ---- entry points outside the headline step, same shapes, reported on their own
