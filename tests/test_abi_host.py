@@ -187,3 +187,22 @@ def test_probe_argument_errors(lib):
     assert lib.ems_probe_copy(d, d, 24, None) == B.EMS_ERR_INVALID_ARG      # not a multiple of 16
     assert lib.ems_probe_copy(C.c_void_p(8), d, 32, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_probe_copy(None, d, 32, None) == B.EMS_ERR_INVALID_ARG
+
+
+def test_binding_rejects_host_tensors_and_wrong_shapes(lib):
+    """The Python layer only marshals: it refuses anything that is not a contiguous device tensor of
+    the documented shape before the library is called (no CPU path exists)."""
+    import torch
+    p = _bad(budget=64)
+    q = torch.zeros((1, 4, 512, 128), dtype=torch.bfloat16)
+    k = torch.zeros((1, 2, 512, 128), dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="device tensor"):
+        B.ems_global_local_score(p, q, k)
+    with pytest.raises(ValueError, match="device tensor"):
+        B.ems_select(p, torch.zeros((1, 2, 512)), torch.zeros((1, 2, 512)))
+    with pytest.raises(ValueError, match="device tensor"):
+        B.ems_evict_merge(p, k, k, torch.zeros((1, 2, 48), dtype=torch.int32), torch.zeros((1, 2, 32), dtype=torch.int32))
+    with pytest.raises(ValueError, match="device tensor"):
+        B.ems_redundancy_rate(p, k, k)
+    with pytest.raises(B.EmsError):
+        B.ems_partition_sizes(_bad(budget=8))
