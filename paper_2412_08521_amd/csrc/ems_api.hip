@@ -49,8 +49,8 @@ void partition_sizes(const ems_params* p, int* n_imp, int* n_tbm)
 }
 
 struct ScorePlan {
-    int n_chunks, chunk_rows, loc_chunk0, n_pad;
-    size_t off_lse2, off_part_glo, off_part_loc, total;
+    int n_chunks, chunk_rows, loc_chunk0, n_pad, p1_splits;
+    size_t off_lse2, off_part_glo, off_part_loc, off_part_m, off_part_l, total;
 };
 
 // Row chunks of the key-stationary pass: small enough that there are a few thousand
@@ -83,6 +83,18 @@ ScorePlan plan_score(const ems_params* p)
         off += align_up(sizeof(float) * (size_t)bkv * s.n_chunks * N);
         s.off_part_loc = off;
         off += align_up(sizeof(float) * (size_t)bkv * (s.n_chunks - s.loc_chunk0) * N);
+    }
+    // Pass 1: a row tile's key range is cut into splits while there are too few row tiles to
+    // balance the causal triangle over the chip (short sequences); partial (max, sum) pairs
+    // are then combined by a small kernel.
+    const int rpb = kpb;                                              // query rows per pass-1 block
+    const long long row_tiles = (long long)p->batch * p->q_heads * ((N + rpb - 1) / rpb);
+    s.p1_splits = 1;
+    while (s.p1_splits < 8 && row_tiles * s.p1_splits < 2048 && (N + rpb - 1) / rpb >= 2 * s.p1_splits) s.p1_splits *= 2;
+    s.off_part_m = off; s.off_part_l = off;
+    if (s.p1_splits > 1) {
+        const size_t one = align_up(sizeof(float) * (size_t)s.p1_splits * p->batch * p->q_heads * s.n_pad);
+        off += one; s.off_part_l = off; off += one;
     }
     s.total = off;
     return s;
@@ -153,6 +165,9 @@ static void fill_score_args(ems::ScoreArgs& a, const ems_params* p, const ScoreP
     a.lse2 = w ? reinterpret_cast<float*>(w + plan.off_lse2) : nullptr;
     a.part_glo = w ? reinterpret_cast<float*>(w + plan.off_part_glo) : nullptr;
     a.part_loc = w ? reinterpret_cast<float*>(w + plan.off_part_loc) : nullptr;
+    a.part_m = w ? reinterpret_cast<float*>(w + plan.off_part_m) : nullptr;
+    a.part_l = w ? reinterpret_cast<float*>(w + plan.off_part_l) : nullptr;
+    a.p1_splits = plan.p1_splits;
     a.batch = p->batch; a.q_heads = p->q_heads; a.kv_heads = p->kv_heads;
     a.head_dim = p->head_dim; a.seq_len = p->seq_len; a.window = p->window;
     a.n_pad = plan.n_pad;

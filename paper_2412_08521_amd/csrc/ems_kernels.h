@@ -23,6 +23,9 @@ struct ScoreArgs {
     int loc_chunk0;     // first chunk that holds a last-window row
     float scale_log2e;  // softmax scale * log2(e)
     int p1_groups, p1_per_group;  // pass-1 work grouping per XCD (set by the launcher)
+    int p1_splits;      // pass 1: key-range splits per row tile (1 = none)
+    float* part_m;      // [p1_splits, B*Hq, n_pad] partial running maxima (workspace, p1_splits > 1)
+    float* part_l;      // [p1_splits, B*Hq, n_pad] partial sums relative to them
 };
 
 struct SelectArgs {

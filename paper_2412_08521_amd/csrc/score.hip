@@ -230,6 +230,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int G = a.q_heads / a.kv_heads;
     int bid = xcd_work_item(a.p1_groups, a.p1_per_group);
     if (bid < 0) return;
+    const int S = a.p1_splits, sp = bid % S; bid /= S;           // this block's share of the key range
     const int g = bid % G; bid /= G;
     const int BKV = a.batch * a.kv_heads;
     int rt, bkv;                                  // bkv = b * kv_heads + kv
@@ -272,19 +273,24 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     };
 
     const int last_key = min(N, (rt + 1) * kRowsPerBlock);      // exclusive
-    const int n_tiles = (last_key + kStageRows - 1) / kStageRows;
+    const int n_all = (last_key + kStageRows - 1) / kStageRows;
+    const int t_begin = (int)((long long)n_all * sp / S), n_tiles = (int)((long long)n_all * (sp + 1) / S);
     const float c = a.scale_log2e;
 
     wait_vmem_all_visible();
     const unsigned lds0 = lds_address(&lds[0][0]);
     StageLane<T, D> sl;
     sl.init();
-    stage_issue<T, D>(sl, lds0, K, 0, N);
-    if (n_tiles > 1) { stage_issue<T, D>(sl, lds0 + Stage<T, D>::kBytes, K, kStageRows, N); wait_vmem<kLoads>(); }
-    else wait_vmem<0>();
-    block_barrier();
+    if (t_begin < n_tiles) {                                      // block-uniform (a split can be empty)
+        stage_issue<T, D>(sl, lds0 + (t_begin % kBuf) * Stage<T, D>::kBytes, K, t_begin * kStageRows, N);
+        if (t_begin + 1 < n_tiles) {
+            stage_issue<T, D>(sl, lds0 + ((t_begin + 1) % kBuf) * Stage<T, D>::kBytes, K, (t_begin + 1) * kStageRows, N);
+            wait_vmem<kLoads>();
+        } else wait_vmem<0>();
+        block_barrier();
+    }
 
-    for (int t = 0; t < n_tiles; ++t) {
+    for (int t = t_begin; t < n_tiles; ++t) {
         // the buffer of stage t+2 was last read in iteration t-1, which every wave has left
         if (t + 2 < n_tiles)
             stage_issue<T, D>(sl, lds0 + ((t + 2) % kBuf) * Stage<T, D>::kBytes, K, (t + 2) * kStageRows, N);
@@ -386,8 +392,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
 
     flush_pend1();
-    float* lse2 = a.lse2 + (size_t)(b * a.q_heads + h) * a.n_pad;
-    float* lse_nat = a.lse_opt ? a.lse_opt + (size_t)(b * a.q_heads + h) * N : nullptr;
+    const size_t bh = (size_t)(b * a.q_heads + h);
+    float* lse2 = a.lse2 + bh * a.n_pad;
+    float* lse_nat = a.lse_opt ? a.lse_opt + bh * N : nullptr;
 #pragma unroll
     for (int s = 0; s < kSub; ++s) {
         const float m_o = __shfl_xor(m_run[s], 32);
@@ -395,12 +402,42 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         const float M = fmaxf(m_run[s], m_o);
         const float Mu = (M == -INFINITY) ? 0.f : M;
         const float L = l_run[s] * exp2_fast(m_run[s] - Mu) + l_o * exp2_fast(m_o - Mu);
-        const float v = Mu + log2_fast(L);
         const int qi = q0 + s * 32 + col;
+        if (S > 1) {
+            // partial (max, sum) of this key range; combined by lse_combine_kernel
+            if (half == 0 && qi < a.n_pad) {
+                a.part_m[((size_t)sp * a.batch * a.q_heads + bh) * a.n_pad + qi] = M;
+                a.part_l[((size_t)sp * a.batch * a.q_heads + bh) * a.n_pad + qi] = L;
+            }
+            continue;
+        }
+        const float v = Mu + log2_fast(L);
         // rows past the end get +inf: the second pass then gives them weight zero
         if (half == 0 && qi < a.n_pad) lse2[qi] = qi < N ? v : INFINITY;
         if (half == 0 && qi < N && lse_nat) lse_nat[qi] = v * 0.693147180559945309f;
     }
+}
+
+// Combines the partial (max, sum) pairs of pass 1's key-range splits into the row
+// log-sum-exp, in split order.
+__global__ __launch_bounds__(256) void lse_combine_kernel(ScoreArgs a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t bh = blockIdx.y, BH = (size_t)a.batch * a.q_heads;
+    if (i >= a.n_pad) return;
+    float v = INFINITY;                                           // rows past the end: weight zero in pass 2
+    if (i < a.seq_len) {
+        float M = -INFINITY;
+        for (int s = 0; s < a.p1_splits; ++s) M = fmaxf(M, a.part_m[((size_t)s * BH + bh) * a.n_pad + i]);
+        float L = 0.f;
+        for (int s = 0; s < a.p1_splits; ++s) {
+            const float m = a.part_m[((size_t)s * BH + bh) * a.n_pad + i];
+            if (m > -INFINITY) L += a.part_l[((size_t)s * BH + bh) * a.n_pad + i] * exp2_fast(m - M);
+        }
+        v = M + log2_fast(L);
+        if (a.lse_opt) a.lse_opt[bh * a.seq_len + i] = v * 0.693147180559945309f;
+    }
+    a.lse2[bh * a.n_pad + i] = v;
 }
 
 // ------------------------------------------------------------------------------------
@@ -710,10 +747,15 @@ static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
     // blocks of one (b, kv-head) stream the same K: one group per XCD when there are enough
     // heads to keep all XCDs busy, else groups of the G q-heads of one row tile
     ScoreArgs a1 = a;
-    if (BKV >= kXcds) { a1.p1_groups = BKV; a1.p1_per_group = n_row_tiles * G; }
-    else { a1.p1_groups = BKV * n_row_tiles; a1.p1_per_group = G; }
+    const int S = a.p1_splits < 1 ? 1 : a.p1_splits;
+    a1.p1_splits = S;
+    if (BKV >= kXcds) { a1.p1_groups = BKV; a1.p1_per_group = n_row_tiles * G * S; }
+    else { a1.p1_groups = BKV * n_row_tiles; a1.p1_per_group = G * S; }
     const unsigned grid1 = xcd_grid(a1.p1_groups, a1.p1_per_group);
     hipLaunchKernelGGL((score_pass1_kernel<T, D>), dim3(grid1), dim3(kBlock), 0, st, a1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || S == 1) return e;
+    hipLaunchKernelGGL(lse_combine_kernel, dim3((a.n_pad + 255) / 256, a.batch * a.q_heads), dim3(256), 0, st, a1);
     return hipGetLastError();
 }
 
