@@ -102,7 +102,8 @@ ScorePlan plan_score(const ems_params* p)
 
 size_t select_ws_bytes(const ems_params* p)
 {
-    return align_up(sizeof(float) * (size_t)p->batch * p->kv_heads * p->seq_len);
+    // ranking keys, and (used by the long-sequence kernel) the Eq. 2 vector before pooling
+    return 2 * align_up(sizeof(float) * (size_t)p->batch * p->kv_heads * p->seq_len);
 }
 
 size_t merge_ws_bytes(const ems_params* p)
@@ -241,6 +242,7 @@ int ems_select(const ems_params* p, const float* s_glo, const float* s_loc,
     ems::SelectArgs a{};
     a.s_glo = s_glo; a.s_loc = s_loc; a.s_gl_opt = s_gl_opt;
     a.pooled = static_cast<float*>(ws);
+    a.comb = reinterpret_cast<float*>(static_cast<char*>(ws) + select_ws_bytes(p) / 2);
     a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
     a.bkv = p->batch * p->kv_heads; a.seq_len = p->seq_len; a.window = p->window;
     a.n_imp = n_imp; a.n_tbm = n_tbm; a.pool_kernel = p->pool_kernel;

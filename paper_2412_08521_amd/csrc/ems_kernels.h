@@ -33,6 +33,7 @@ struct SelectArgs {
     const float* s_loc;
     float* s_gl_opt;    // nullable
     float* pooled;      // [B*Hkv, N] workspace (ranking keys)
+    float* comb;        // [B*Hkv, N] workspace (Eq. 2 vector before pooling; long sequences only)
     int32_t* imp_idx;
     int32_t* tbm_idx;
     int bkv, seq_len, window, n_imp, n_tbm, pool_kernel;

@@ -18,6 +18,7 @@ namespace ems {
 
 constexpr int kSelBlock = 1024;
 constexpr int kSelWaves = kSelBlock / kWave;
+constexpr int kSelUnroll = 8;     // keys in flight per thread in the loops that re-read them from memory
 
 // Monotone map float -> uint32 (larger float <=> larger integer), also for negatives.
 __device__ __forceinline__ uint32_t order_key(float x)
@@ -74,14 +75,18 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
     for (int w = 0; w < kSelWaves; ++w) { tot_g += red[w][0]; tot_l += red[w][1]; }
     const float align = (tot_l / (float)N) / (tot_g / (float)N);
 
-    // ---- 2. element-wise max and mean pooling (zero padding, divisor = kernel width)
+    // ---- 2. element-wise max, staged through the workspace, then mean pooling (zero padding,
+    // divisor = kernel width)
+    float* comb = a.comb + (size_t)blockIdx.x * N;
+    for (int j = tid; j < N; j += kSelBlock) comb[j] = fmaxf(glo[j] * align, loc[j]);
+    __syncthreads();   // this block's global writes are visible to the whole block
     const int half = (a.pool_kernel - 1) / 2;
     const float inv_div = (float)a.pool_kernel;
     for (int j = tid; j < N; j += kSelBlock) {
         float acc = 0.f;
         for (int t = -half; t <= half; ++t) {
             const int jj = j + t;
-            if (jj >= 0 && jj < N) acc += fmaxf(glo[jj] * align, loc[jj]);
+            if (jj >= 0 && jj < N) acc += comb[jj];
         }
         const float v = acc / inv_div;
         pooled[j] = v;
@@ -98,13 +103,26 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
         if (tid < 512) hist[tid >> 8][tid & 255] = 0;
         __syncthreads();
         const uint32_t p0 = sel_prefix[0], p1 = sel_prefix[1];
-        for (int j = tid; j < Nc; j += kSelBlock) {
-            const uint32_t key = order_key(pooled[j]);
-            const uint32_t hi = shift == 24 ? 0u : (key >> (shift + 8));
-            const int digit = (key >> shift) & 255;
-            hist_add(hist[0], digit, shift == 24 || hi == p0);
-            hist_add(hist[1], digit, shift == 24 || hi == p1);
+        const bool same_prefix = shift == 24 || p0 == p1;
+        // eight keys in flight per thread: the loop is bound by load latency otherwise
+        for (int j0 = tid; j0 < Nc; j0 += kSelBlock * kSelUnroll) {
+            uint32_t key[kSelUnroll];
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const int j = j0 + u * kSelBlock;
+                key[u] = j < Nc ? order_key(pooled[j]) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const bool ok = j0 + u * kSelBlock < Nc;
+                const uint32_t hi = shift == 24 ? 0u : (key[u] >> (shift + 8));
+                const int digit = (key[u] >> shift) & 255;
+                hist_add(hist[0], digit, ok && (shift == 24 || hi == p0));
+                if (!same_prefix) hist_add(hist[1], digit, ok && hi == p1);
+            }
         }
+        __syncthreads();
+        if (same_prefix && tid < 256) hist[1][tid] = hist[0][tid];   // one count serves both cuts
         __syncthreads();
         // suffix[t][d] = number of matching keys with digit >= d: an inclusive scan over
         // the digits taken from 255 downwards, 256 threads per target (4 waves each).
@@ -162,11 +180,19 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
     };
     // pass A: how many keys equal to each cut value does every wave hold
     int eq1 = 0, eq2 = 0;
-    for (int j = w0 + lane; j < w1 + lane; j += kWave) {
-        const bool ok = j < w1;
-        const uint32_t key = ok ? order_key(pooled[j]) : 0u;
-        eq1 += __popcll(__ballot(ok && key == T1));
-        eq2 += __popcll(__ballot(ok && key == T2));
+    for (int j0 = w0 + lane; j0 < w1 + lane; j0 += kWave * kSelUnroll) {
+        uint32_t key[kSelUnroll];
+#pragma unroll
+        for (int u = 0; u < kSelUnroll; ++u) {
+            const int j = j0 + u * kWave;
+            key[u] = j < w1 ? order_key(pooled[j]) : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kSelUnroll; ++u) {
+            const bool ok = j0 + u * kWave < w1;
+            eq1 += __popcll(__ballot(ok && key[u] == T1));
+            eq2 += __popcll(__ballot(ok && key[u] == T2));
+        }
     }
     int o1, o2, tot;
     wave_prefix(eq1, o1, tot);
@@ -185,13 +211,22 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
     int c_imp = 0, c_tbm = 0;
     {
         int r1 = o1, r2 = o2;
-        for (int j = w0 + lane; j < w1 + lane; j += kWave) {
-            const bool ok = j < w1;
-            const uint32_t key = ok ? order_key(pooled[j]) : 0u;
-            bool ii, tt;
-            classify(key, ok, r1, r2, ii, tt);
-            c_imp += __popcll(__ballot(ii));
-            c_tbm += __popcll(__ballot(tt));
+        for (int j0 = w0 + lane; j0 < w1 + lane; j0 += kWave * kSelUnroll) {
+            uint32_t key[kSelUnroll];
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const int j = j0 + u * kWave;
+                key[u] = j < w1 ? order_key(pooled[j]) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const bool ok = j0 + u * kWave < w1;
+                if (__ballot(ok && key[u] >= T2) == 0ull) continue;   // wave-uniform: nothing to rank here
+                bool ii, tt;
+                classify(key[u], ok, r1, r2, ii, tt);
+                c_imp += __popcll(__ballot(ii));
+                c_tbm += __popcll(__ballot(tt));
+            }
         }
     }
     int bi, bt;
@@ -202,15 +237,25 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
     int32_t* tbm = a.tbm_idx ? a.tbm_idx + (size_t)blockIdx.x * a.n_tbm : nullptr;
     {
         int r1 = o1, r2 = o2;
-        for (int j = w0 + lane; j < w1 + lane; j += kWave) {
-            const bool ok = j < w1;
-            const uint32_t key = ok ? order_key(pooled[j]) : 0u;
-            bool ii, tt;
-            classify(key, ok, r1, r2, ii, tt);
-            const unsigned long long mi = __ballot(ii), mt = __ballot(tt);
-            if (ii) { const int at = bi + __popcll(mi & below); if (at < a.n_imp) imp[at] = j; }
-            if (tt && tbm) { const int at = bt + __popcll(mt & below); if (at < a.n_tbm) tbm[at] = j; }
-            bi += __popcll(mi); bt += __popcll(mt);
+        for (int j0 = w0 + lane; j0 < w1 + lane; j0 += kWave * kSelUnroll) {
+            uint32_t key[kSelUnroll];
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const int j = j0 + u * kWave;
+                key[u] = j < w1 ? order_key(pooled[j]) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kSelUnroll; ++u) {
+                const int j = j0 + u * kWave;
+                const bool ok = j < w1;
+                if (__ballot(ok && key[u] >= T2) == 0ull) continue;   // wave-uniform
+                bool ii, tt;
+                classify(key[u], ok, r1, r2, ii, tt);
+                const unsigned long long mi = __ballot(ii), mt = __ballot(tt);
+                if (ii) { const int at = bi + __popcll(mi & below); if (at < a.n_imp) imp[at] = j; }
+                if (tt && tbm) { const int at = bt + __popcll(mt & below); if (at < a.n_tbm) tbm[at] = j; }
+                bi += __popcll(mi); bt += __popcll(mt);
+            }
         }
     }
 }
