@@ -174,12 +174,14 @@ def test_decode_invariants_over_many_steps():
     n_imp, n_tbm = B.ems_partition_sizes(p)
     E, W, N = n_imp + n_tbm, p.window, p.seq_len
     g = torch.Generator(device="cpu").manual_seed(1)
-    steps = 3 * W + 5
+    steps = 40 * W + 5                                  # long enough for every entry to be replaced several times
+    qs = torch.randn((steps, p.batch, p.q_heads, p.head_dim), generator=g).to(torch.bfloat16).cuda()
+    ks = torch.randn((steps, p.batch, p.kv_heads, p.head_dim), generator=g).to(torch.bfloat16).cuda()
+    vs = torch.randn((steps, p.batch, p.kv_heads, p.head_dim), generator=g).to(torch.bfloat16).cuda()
+    ws = torch.empty(max(B.ems_decode_workspace_bytes(p), 256), dtype=torch.uint8, device="cuda")
+    out = None
     for t in range(steps):
-        q = torch.randn((p.batch, p.q_heads, p.head_dim), generator=g).to(torch.bfloat16).cuda()
-        k = torch.randn((p.batch, p.kv_heads, p.head_dim), generator=g).to(torch.bfloat16).cuda()
-        v = torch.randn((p.batch, p.kv_heads, p.head_dim), generator=g).to(torch.bfloat16).cuda()
-        B.ems_decode_step(p, st, t, q, k, v)
+        out = B.ems_decode_step(p, st, t, qs[t], ks[t], vs[t], ws=ws, out=out)
     torch.cuda.synchronize()
     rows, pos = _np(st.tok_row), _np(st.tok_pos)
     for b in range(p.batch):
