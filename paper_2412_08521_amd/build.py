@@ -24,6 +24,35 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Wall", "-Wno-unused-function",
          # the LDS-DMA inline assembly names M0 as clobbered, which clang flags as reserved
          "-Wno-inline-asm"] + os.environ.get("EMS_EXTRA_HIPCC_FLAGS", "").split()
+# The score kernels read every accumulator element with the vector ALU: matrix results go to
+# ordinary vector registers, never to the accumulation file (which the ALU cannot read).
+FILE_FLAGS = {"score.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Rpass-analysis=kernel-resource-usage"]}
+# Kernels that count their own vector-memory operations (s_waitcnt vmcnt(n) by hand around the
+# LDS DMA): a register spill would add scratch loads/stores the count does not know about, so
+# such a build is rejected instead of being allowed to run with a silent race.
+NO_SCRATCH = {"score.hip": ("score_pass1", "score_pass2")}
+
+
+def _check_no_scratch(src: str, remarks: str) -> None:
+    """Parse the compiler's kernel-resource-usage remarks; raise if a guarded kernel spills."""
+    guarded = NO_SCRATCH.get(src, ())
+    name, seen = None, set()
+    for line in remarks.splitlines():
+        if "remark:" not in line:
+            continue
+        text = line.split("remark:", 1)[1].strip()
+        if text.startswith("Function Name:"):
+            name = text.split(":", 1)[1].split("[")[0].strip()
+        elif name and any(g in name for g in guarded):
+            for key in ("ScratchSize [bytes/lane]:", "VGPRs Spill:", "SGPRs Spill:"):
+                if text.startswith(key):
+                    val = int(text[len(key):].split("[")[0].strip())
+                    seen.add(name)
+                    if val != 0:
+                        raise RuntimeError(f"{src}: kernel {name} reports '{key} {val}'; the hand-counted "
+                                           "s_waitcnt vmcnt() of its DMA pipeline requires zero scratch")
+    if guarded and not seen:
+        raise RuntimeError(f"{src}: no resource-usage remark found for kernels {guarded}")
 
 
 def _stale(out: str, deps) -> bool:
@@ -41,12 +70,20 @@ def build(force: bool = False, verbose: bool = False) -> str:
         s = os.path.join(CSRC, src)
         o = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
         if force or _stale(o, [s] + hdrs):
-            cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
+            cmd = [HIPCC] + FLAGS + FILE_FLAGS.get(src, []) + ["-c", s, "-o", o]
             r = subprocess.run(cmd, capture_output=True, text=True)
             err = "\n".join(l for l in r.stderr.splitlines()
                             if "packed-fp32-ops' is not a recognized feature" not in l)
             if r.returncode != 0:
                 raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+            if src in NO_SCRATCH:
+                try:
+                    _check_no_scratch(src, err)
+                except RuntimeError:
+                    os.remove(o)          # never link an object that failed the check
+                    raise
+                err = "\n".join(l for l in err.splitlines() if "kernel-resource-usage" not in l
+                                and not l.lstrip().startswith(("|", "^")) and "{" != l.strip()[-1:])
             if verbose and err.strip():
                 print(err, file=sys.stderr)
         return o

@@ -4,6 +4,7 @@
 #include "ems_kernels.h"
 
 #include <cmath>
+#include <cstdlib>
 
 namespace {
 
@@ -69,8 +70,9 @@ ScorePlan plan_score(const ems_params* p)
         for (int J = 0; J < n_key_tiles; ++J) t += nI - (int)(((long long)J * kpb) / R);
         return t * bkv;
     };
+    const char* old_p2 = std::getenv("EMS_P2_OLD");
     int R = 4096;
-    while (R > 512 && items(R) < 2048) R >>= 1;
+    while (R > 512 && items(R) < (old_p2 ? 2048 : 16384)) R >>= 1;
     s.chunk_rows = R;
     s.n_chunks = (N + R - 1) / R;
     s.loc_chunk0 = (N - p->window) / R;

@@ -12,6 +12,9 @@
 #include "ems_common.h"
 #include "ems_kernels.h"
 
+#include <cstdlib>
+#include <type_traits>
+
 namespace ems {
 
 constexpr int kWavesPerBlock = 4;
@@ -61,6 +64,14 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsig
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(m0v) : "memory", "m0");
     else
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(m0v) : "memory", "m0");
+}
+
+// The value itself, made opaque to the optimiser (stops loop-invariant code motion of what is
+// computed from it).
+__device__ __forceinline__ int opaque_lane(int v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
 }
 
 // LDS byte address of a __shared__ object.
@@ -265,7 +276,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     f32x16_t pend;
 #pragma unroll
     for (int r = 0; r < 16; ++r) pend[r] = -INFINITY;
-    auto flush_pend1 = [&]() {
+    auto flush_pend1 = [&]() __attribute__((always_inline)) {
         float tot = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { tot += exp2_fast(pend[r]); pend[r] = -INFINITY; }
@@ -541,7 +552,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     f32x16_t pend;
 #pragma unroll
     for (int r = 0; r < 16; ++r) pend[r] = -INFINITY;
-    auto flush_pend = [&]() {
+    auto flush_pend = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) { part[kSub - 1][r % (16 / kFrags)] += exp2_fast(pend[r]); pend[r] = -INFINITY; }
     };
@@ -551,20 +562,20 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const float c = a.scale_log2e;
     const int win0 = N - W;
 
-    auto q_of = [&](int t) {
+    auto q_of = [&](int t) __attribute__((always_inline)) {
         const int g = t / tiles_per_head;
         return reinterpret_cast<const T*>(a.q) + ((size_t)(b * a.q_heads + kvh * G + g) * N) * D;
     };
-    auto lse_of = [&](int t) {
+    auto lse_of = [&](int t) __attribute__((always_inline)) {
         const int g = t / tiles_per_head;
         return a.lse2 + (size_t)(b * a.q_heads + kvh * G + g) * a.n_pad;   // padded with +inf
     };
-    auto row0_of = [&](int t) { return r_begin + (t % tiles_per_head) * kStageRows; };
+    auto row0_of = [&](int t) __attribute__((always_inline)) { return r_begin + (t % tiles_per_head) * kStageRows; };
     const unsigned lds0 = lds_address(&lds[0][0]);
     const unsigned lse0 = lds_address(&lds_lse[0][0][0]) + wave * kStageRows * 4;
     StageLane<T, D> sl;
     sl.init();
-    auto issue = [&](int t) {
+    auto issue = [&](int t) __attribute__((always_inline)) {
         stage_issue<T, D>(sl, lds0 + (t % kBuf) * Stage<T, D>::kBytes, q_of(t), row0_of(t), N);
         if (kStageRows == kWave || lane < kStageRows)
             dma_to_lds<4>(lse_of(t), (unsigned)(row0_of(t) + lane) * 4u,
@@ -734,9 +745,339 @@ __global__ __launch_bounds__(256) void lse_to_base2_kernel(ScoreArgs a)
         i < a.seq_len ? a.lse_in_nat[(size_t)bh * a.seq_len + i] * 1.44269504088896340736f : INFINITY;
 }
 
+
+// ------------------------------------------------------------------------------------
+// Pass 2, wave-private form.  A work item is ONE wave: it keeps 32 * kSub keys of one
+// kv-head in registers (MFMA B operand, keys -> lanes) for its whole life and streams the
+// query rows of one row chunk, 32 at a time, through an LDS ring that only this wave
+// touches (DMA by this wave, read by this wave): no workgroup barrier anywhere.  One wave
+// per SIMD owns the whole register file, so the stationary tile is large and every staged
+// row is used for kSub MFMA tiles.
+//
+// The rows of a chunk fall in two classes, handled by two loops that share the ring:
+//   edge rows      stages that touch the diagonal of this wave's keys or the last window:
+//                  tiles are masked, skipped when above the diagonal, and (window rows) also
+//                  added to the local score; a plain loop, one tile at a time;
+//   interior rows  every row sees every key and no row is in the window: one software
+//                  pipeline across tiles and stages, in which the MFMA chain of tile n+1 is
+//                  interleaved with the exp2 / add work of tile n and the next stage's row
+//                  operand and log-sum-exp are fetched from LDS into a second register set.
+// ------------------------------------------------------------------------------------
+template <typename T> struct Stream { static constexpr int kSub = 6; static constexpr int kRing = 4; };
+template <> struct Stream<float> { static constexpr int kSub = 2; static constexpr int kRing = 3; };
+constexpr int kStreamRows = 32;            // query rows per stage (one MFMA row tile)
+
+template <typename T, int D>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void score_pass2_stream_kernel(ScoreArgs a)
+{
+    constexpr int kSub = Stream<T>::kSub, kRing = Stream<T>::kRing;
+    constexpr int kFrags = Tile<T, D>::kFrags;
+    constexpr int kEps = 16 / kFrags;                       // accumulator elements handled per MFMA slot
+    static_assert(kFrags >= 2 && kFrags <= 16 && 16 % kFrags == 0, "slot schedule needs 2..16 fragments per row");
+    static_assert(kSub >= 2 && kSub % 2 == 0, "tiles alternate between two accumulators across stages");
+    constexpr int kRowBytes = Tile<T, D>::kRowBytes;
+    constexpr int kCpr = Tile<T, D>::kChunksPerRow;
+    constexpr int kStageBytes = kStreamRows * kRowBytes;
+    constexpr int kQInstr = kStageBytes / 1024;             // 16-byte DMA instructions per stage
+    constexpr int kLoads = kQInstr + 1;                     // + one 4-byte DMA for the rows' log-sum-exp
+    static_assert((kRing - 1) * kLoads < 64, "vmcnt is a 6-bit counter");
+    static_assert(kRing == 3 || kRing == 4, "the waits below are written for rings of 3 or 4 stages");
+    constexpr int kKeys = 32 * kSub;
+
+    __shared__ __attribute__((aligned(1024))) char lds_q[kRing][kStageBytes];
+    __shared__ __attribute__((aligned(256))) float lds_lse[kRing][2 * kStreamRows];   // second half: spare
+
+    const int N = a.seq_len, W = a.window;
+    const int G = a.q_heads / a.kv_heads;
+    const int n_key_tiles = (N + kKeys - 1) / kKeys;
+    const int n_chunks = a.n_chunks, R = a.chunk_rows;
+
+    int bid = xcd_work_item(a.batch * a.kv_heads * n_chunks, n_key_tiles);
+    if (bid < 0) return;
+    const int J = bid % n_key_tiles; bid /= n_key_tiles;
+    const int BKV = a.batch * a.kv_heads;
+    const int bkv = bid % BKV;
+    const int I = n_chunks - 1 - bid / BKV;                 // heaviest row chunks first
+    const int key_base = J * kKeys;
+    const int r_begin = max(I * R, key_base);               // both multiples of 32
+    const int r_end = min((I + 1) * R, N);
+    if (r_begin >= r_end) return;                           // pair above the diagonal
+    // [r_begin, e_end) touches the diagonal, [e_end, i_end) is interior, [i_end, r_end) holds
+    // window rows (each range may be empty; all bounds but r_end are multiples of 32)
+    const int win0 = N - W;
+    int e_end = min(max(r_begin, min(key_base + kKeys, (win0 / kStreamRows) * kStreamRows)), r_end);
+    const int i_end = min(max(e_end, (win0 / kStreamRows) * kStreamRows), r_end);
+    // the interior loop takes its stages in pairs: when their number is odd, one more row tile
+    // of every q-head is handled by the edge loop (which is correct for any row)
+    if ((((i_end - e_end) / kStreamRows) * G) & 1) e_end += kStreamRows;
+
+    const int b = bkv / a.kv_heads, kvh = bkv % a.kv_heads;
+    const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
+    const T* Q0 = reinterpret_cast<const T*>(a.q) + ((size_t)(b * a.q_heads + kvh * G) * N) * D;
+    const float* L0 = a.lse2 + (size_t)(b * a.q_heads + kvh * G) * a.n_pad;
+
+    const int lane = threadIdx.x;
+    const int col = lane & 31, half = lane >> 5;
+
+    frag_t bk[kSub][kFrags];
+#pragma unroll
+    for (int s = 0; s < kSub; ++s) {
+        const int kj = key_base + s * 32 + col;
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f)
+            bk[s][f] = load_frag_or_zero(K, (size_t)kj * kRowBytes + f * 32 + half * 16, kj < N);
+    }
+    // The stationary operand lives in the accumulation registers, which only the matrix
+    // instructions read: the ordinary vector registers stay free for what the ALU touches.
+#pragma unroll
+    for (int s = 0; s < kSub; ++s)
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f) asm volatile("" : "+a"(bk[s][f]));
+
+    // per-lane constants: DMA source offsets inside a stage (kept in registers when a stage is
+    // few instructions; recomputed per stage otherwise, which only the wide-row validation
+    // type needs) and the LDS offsets of this lane's operand fragments
+    constexpr bool kKeepDmaOff = kQInstr <= 8;
+    auto dma_src_off = [&](int j, int ln) __attribute__((always_inline)) {
+        const int slot = j * kWave + ln, row = slot / kCpr;
+        return (unsigned)row * kRowBytes + (unsigned)(((slot % kCpr) ^ swz_key<T, D>(row)) << 4);
+    };
+    unsigned dma_off[kKeepDmaOff ? kQInstr : 1];
+    if (kKeepDmaOff) {
+#pragma unroll
+        for (int j = 0; j < kQInstr; ++j) dma_off[j] = dma_src_off(j, lane);
+    }
+    unsigned frag_off[kFrags];
+#pragma unroll
+    for (int f = 0; f < kFrags; ++f)
+        frag_off[f] = (unsigned)col * kRowBytes + (unsigned)(((f * 2 + half) ^ swz_key<T, D>(col)) << 4);
+
+    const float c = a.scale_log2e;
+    const unsigned lds_q0 = lds_address(&lds_q[0][0]);
+    const unsigned lds_l0 = lds_address(&lds_lse[0][0]);
+
+    // DMA of the 32 rows starting at `row` of q-head g of the group into ring slot `slot`
+    auto issue = [&](int g, int row, int slot, auto in_range_c) __attribute__((always_inline)) {
+        constexpr bool kInRange = decltype(in_range_c)::value;   // caller knows row + 32 <= N
+        const char* qg = reinterpret_cast<const char*>(Q0) + (size_t)g * N * kRowBytes;
+        const unsigned dst = lds_q0 + slot * kStageBytes;
+        int ln = lane;
+        if (!kKeepDmaOff) ln = opaque_lane(ln);             // keeps the offsets from being hoisted into registers
+        if (kInRange || row + kStreamRows <= N) {
+            const char* base = qg + (size_t)row * kRowBytes;
+#pragma unroll
+            for (int j = 0; j < kQInstr; ++j)
+                dma_to_lds<16>(base, kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln), dst + j * 1024);
+        } else {                                            // rows past the end re-read the last row
+#pragma unroll
+            for (int j = 0; j < kQInstr; ++j) {
+                const int r = (j * kWave + lane) / kCpr;
+                const int over = max(row + r - (N - 1), 0);
+                const unsigned off = kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln);
+                dma_to_lds<16>(qg, (unsigned)row * kRowBytes + off - (unsigned)over * kRowBytes, dst + j * 1024);
+            }
+        }
+        // the rows' log-sum-exp (padded with +inf up to n_pad); both half-waves fetch the same 32
+        // values, the upper half into the spare half of the slot, so that no lane is masked off
+        dma_to_lds<4>(L0 + (size_t)g * a.n_pad, (unsigned)(row + col) * 4u, lds_l0 + slot * (2 * kStreamRows * 4));
+    };
+    // with stages issued up to `last`, wait until stage t has landed (stages complete in order)
+    auto wait_landed = [&](int t, int last) __attribute__((always_inline)) {
+        const int later = last - t;
+        if (later >= 2 && kRing > 3) wait_vmem<2 * kLoads>();
+        else if (later >= 1) wait_vmem<kLoads>();
+        else wait_vmem<0>();
+    };
+
+    float part[kSub][kEps], loc[kSub];
+#pragma unroll
+    for (int s = 0; s < kSub; ++s) {
+        loc[s] = 0.f;
+#pragma unroll
+        for (int e = 0; e < kEps; ++e) part[s][e] = 0.f;
+    }
+
+    wait_vmem_all_visible();
+
+    // ---- edge rows: [r_begin, e_end) and [i_end, r_end) of every q-head of the group
+    {
+        const int lead = (e_end - r_begin) / kStreamRows;
+        const int per_head = lead + (r_end - i_end + kStreamRows - 1) / kStreamRows;
+        const int n_stages = per_head * G;
+        auto row_of = [&](int t) __attribute__((always_inline)) {
+            const int u = t % per_head;
+            return u < lead ? r_begin + u * kStreamRows : i_end + (u - lead) * kStreamRows;
+        };
+        for (int t = 0; t < kRing - 1 && t < n_stages; ++t) issue(t / per_head, row_of(t), t % kRing, std::false_type{});
+        for (int t = 0; t < n_stages; ++t) {
+            if (t + kRing - 1 < n_stages)
+                issue((t + kRing - 1) / per_head, row_of(t + kRing - 1), (t + kRing - 1) % kRing, std::false_type{});
+            wait_landed(t, min(n_stages - 1, t + kRing - 1));
+            const char* qs = lds_q[t % kRing];
+            const float* ls = lds_lse[t % kRing];
+            frag_t aq[kFrags];
+            float lse_r[16];
+#pragma unroll
+            for (int f = 0; f < kFrags; ++f) aq[f] = *reinterpret_cast<const frag_t*>(qs + frag_off[f]);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ls + 8 * q4 + 4 * half);
+                lse_r[4 * q4 + 0] = v[0]; lse_r[4 * q4 + 1] = v[1]; lse_r[4 * q4 + 2] = v[2]; lse_r[4 * q4 + 3] = v[3];
+            }
+            const int row0 = row_of(t);
+#pragma unroll
+            for (int ks = 0; ks < kSub; ++ks) {
+                const int ks0 = key_base + ks * 32;
+                if (row0 + 31 >= ks0)                        // wave-uniform: not entirely above the diagonal
+                    pass2_tile<T, D, true>(aq, bk[ks], lse_r, c, part[ks][0], loc[ks], row0, ks0 + col, half, win0);
+                __builtin_amdgcn_sched_barrier(0);           // one tile's temporaries at a time
+            }
+            // the slot is re-filled by the DMA issued at the top of the next iteration: the
+            // fragments above are in registers by then (their uses wait for them)
+        }
+        wait_vmem<0>();
+    }
+
+    // ---- interior rows: [e_end, i_end) of every q-head, one pipeline over all tiles.  The loop
+    // body is straight-line code (an even number of stages, DMA issued for every stage index --
+    // past the end the last stage is fetched again into a ring slot nobody reads -- and a constant
+    // wait count), so nothing in it can be moved out of the slot it was written in.
+    if (e_end < i_end) {
+        const int per_head = (i_end - e_end) / kStreamRows;
+        const int n_stages = per_head * G;                  // even
+
+        frag_t aq[2][kFrags];
+        float lse_r[2][16];
+        f32x16_t acc[2];
+        float xp[kEps];                                     // exponents whose exp2 is still owed
+        auto fetch = [&](int t, auto set_c) __attribute__((always_inline)) {   // LDS -> register set of stage t
+            constexpr int set = decltype(set_c)::value;
+            const char* qs = lds_q[t % kRing];
+            const float* ls = lds_lse[t % kRing];
+#pragma unroll
+            for (int f = 0; f < kFrags; ++f) aq[set][f] = *reinterpret_cast<const frag_t*>(qs + frag_off[f]);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ls + 8 * q4 + 4 * half);
+                lse_r[set][4 * q4 + 0] = v[0]; lse_r[set][4 * q4 + 1] = v[1];
+                lse_r[set][4 * q4 + 2] = v[2]; lse_r[set][4 * q4 + 3] = v[3];
+            }
+        };
+        // issue cursor: stage number, q-head and first row of the next stage to fetch
+        int u_next = 0, g_next = 0, row_next = e_end;
+        auto issue_next = [&]() __attribute__((always_inline)) {
+            issue(g_next, row_next, u_next % kRing, std::true_type{});
+            ++u_next;
+            const bool more = u_next < n_stages;            // else: stay on the last stage
+            const bool wrap = row_next + kStreamRows >= i_end;
+            const int row_adv = wrap ? e_end : row_next + kStreamRows;
+            g_next = more && wrap ? g_next + 1 : g_next;
+            row_next = more ? row_adv : row_next;
+        };
+
+#pragma unroll
+        for (int i = 0; i < kRing - 1; ++i) issue_next();
+        wait_vmem<(kRing - 2) * kLoads>();
+        fetch(0, std::integral_constant<int, 0>{});
+        // The pipeline starts on a tile that weighs nothing: a zero accumulator under an
+        // infinite log-sum-exp, and owed exponents of -inf.
+        acc[1] = zero_acc();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) lse_r[1][r] = INFINITY;
+#pragma unroll
+        for (int e = 0; e < kEps; ++e) xp[e] = -INFINITY;
+
+        // One stage: tile ks runs its MFMA chain into acc[ks & 1] while the vector ALU turns the
+        // tile before it (acc[1 - (ks & 1)]; for ks = 0 the last tile of the previous stage, whose
+        // rows' log-sum-exp is in the other register set) into weights.  Slot f of a chain does
+        // the exp2 of the elements whose exponents were formed in slot f - 1, so the first read
+        // of an accumulator comes a full slot after the chain that wrote it has ended.
+        auto stage = [&](int t, auto set_c) __attribute__((always_inline)) {
+            constexpr int set = decltype(set_c)::value;
+            issue_next();                                   // stage t + kRing - 1
+#pragma unroll
+            for (int ks = 0; ks < kSub; ++ks) {
+                constexpr int kLast = kFrags - 1;
+                const int ps = (ks + kSub - 1) % kSub;       // key subtile of the tile being weighed
+                const int pps = (ks + kSub - 2) % kSub;      // key subtile the owed exponents belong to
+                f32x16_t& cur = acc[ks & 1];
+                const f32x16_t& prev = acc[1 - (ks & 1)];
+                const float (&pl)[16] = lse_r[ks == 0 ? 1 - set : set];
+#pragma unroll
+                for (int f = 0; f < kFrags; ++f) {
+                    if (f == 0) mma_first<T>(cur, aq[set][0], bk[ks][0]);
+                    else mma<T>(cur, aq[set][f], bk[ks][f]);
+                    if (f == 0) {
+#pragma unroll
+                        for (int e = 0; e < kEps; ++e) part[pps][e] += exp2_fast(xp[e]);
+                        // the previous stage's register set is free from here on; stage t + 1 has
+                        // landed once only the kRing - 2 stages issued after it are in flight
+                        if (ks == 1) {
+                            wait_vmem<(kRing - 2) * kLoads>();
+                            fetch(t + 1, std::integral_constant<int, 1 - set>{});
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < kEps; ++e) {
+                            const int r = (f - 1) * kEps + e;
+                            part[ps][e] += exp2_fast(__builtin_fmaf(prev[r], c, -pl[r]));
+                        }
+                    }
+                    if (f == kLast) {
+#pragma unroll
+                        for (int e = 0; e < kEps; ++e) {
+                            const int r = kLast * kEps + e;
+                            xp[e] = __builtin_fmaf(prev[r], c, -pl[r]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        for (int t = 0; t < n_stages; t += 2) {
+            stage(t, std::integral_constant<int, 0>{});
+            stage(t + 1, std::integral_constant<int, 1>{});
+        }
+        // the last tile (key subtile kSub - 1 of the last stage, register set 1) and the owed exponents
+#pragma unroll
+        for (int e = 0; e < kEps; ++e) part[kSub - 2][e] += exp2_fast(xp[e]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            part[kSub - 1][r % kEps] += exp2_fast(__builtin_fmaf(acc[1][r], c, -lse_r[1][r]));
+        wait_vmem<0>();                                     // no DMA may outlive the wave's LDS
+    }
+
+    const int loc_chunk0 = a.loc_chunk0;
+    float* out_glo = a.n_chunks == 1 ? a.s_glo + (size_t)bkv * N
+                                     : a.part_glo + ((size_t)bkv * n_chunks + I) * N;
+    float* out_loc = nullptr;
+    if (a.n_chunks == 1) out_loc = a.s_loc + (size_t)bkv * N;
+    else if (I >= loc_chunk0)
+        out_loc = a.part_loc + ((size_t)bkv * (n_chunks - loc_chunk0) + (I - loc_chunk0)) * N;
+#pragma unroll
+    for (int s = 0; s < kSub; ++s) {
+        float g = part[s][0];
+#pragma unroll
+        for (int e = 1; e < kEps; ++e) g += part[s][e];
+        const float gsum = g + __shfl_xor(g, 32);           // the half-waves hold disjoint rows of the same keys
+        const float lsum = loc[s] + __shfl_xor(loc[s], 32);
+        const int kj = key_base + s * 32 + col;
+        if (half == 0 && kj < N) {
+            out_glo[kj] = gsum;
+            if (out_loc) out_loc[kj] = lsum;
+        }
+    }
+}
+
 template <typename T> static int keys_per_block() { return kWavesPerBlock * 32 * Sub<T>::kSub; }
 
-int score_keys_per_block(int dtype_is_f32) { return dtype_is_f32 ? keys_per_block<float>() : keys_per_block<bf16_t>(); }
+static bool use_old_pass2() { static const bool v = std::getenv("EMS_P2_OLD") != nullptr; return v; }   // development switch
+
+int score_keys_per_block(int dtype_is_f32)
+{
+    if (use_old_pass2()) return dtype_is_f32 ? keys_per_block<float>() : keys_per_block<bf16_t>();
+    return 32 * (dtype_is_f32 ? Stream<float>::kSub : Stream<bf16_t>::kSub);
+}
 
 template <typename T, int D>
 static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
@@ -770,13 +1111,22 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
         hipLaunchKernelGGL(lse_to_base2_kernel, g, dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     }
-    const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_key_tiles);
-    hipLaunchKernelGGL((score_pass2_kernel<T, D>), dim3(grid2), dim3(kBlock), 0, st, a);
-    hipError_t e = hipGetLastError();
+    const bool use_old = use_old_pass2();
+    hipError_t e;
+    if (use_old) {
+        const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_key_tiles);
+        hipLaunchKernelGGL((score_pass2_kernel<T, D>), dim3(grid2), dim3(kBlock), 0, st, a);
+        e = hipGetLastError();
+    } else {
+        const int n_tiles_w = (a.seq_len + 32 * Stream<T>::kSub - 1) / (32 * Stream<T>::kSub);
+        const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_tiles_w);
+        hipLaunchKernelGGL((score_pass2_stream_kernel<T, D>), dim3(grid2), dim3(kWave), 0, st, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
         dim3 g((a.seq_len + 255) / 256, BKV);
-        hipLaunchKernelGGL(score_reduce_kernel, g, dim3(256), 0, st, a, kKeys);
+        hipLaunchKernelGGL(score_reduce_kernel, g, dim3(256), 0, st, a, use_old ? kKeys : 32 * Stream<T>::kSub);
         e = hipGetLastError();
     }
     return e;
