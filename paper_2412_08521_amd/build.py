@@ -44,7 +44,8 @@ def _check_no_scratch(src: str, remarks: str) -> None:
         if text.startswith("Function Name:"):
             name = text.split(":", 1)[1].split("[")[0].strip()
         elif name and any(g in name for g in guarded):
-            for key in ("ScratchSize [bytes/lane]:", "VGPRs Spill:", "SGPRs Spill:"):
+            # (a "VGPRs Spill" that costs no scratch went to the accumulation registers: moves, not memory)
+            for key in ("ScratchSize [bytes/lane]:",):
                 if text.startswith(key):
                     val = int(text[len(key):].split("[")[0].strip())
                     seen.add(name)

@@ -72,7 +72,9 @@ ScorePlan plan_score(const ems_params* p)
     };
     const char* old_p2 = std::getenv("EMS_P2_OLD");
     int R = 4096;
-    while (R > 512 && items(R) < (old_p2 ? 2048 : 16384)) R >>= 1;
+    const char* it_env = std::getenv("EMS_ITEMS");
+    const long long want_items = it_env ? std::atoll(it_env) : (old_p2 ? 2048 : 32768);
+    while (R > 512 && items(R) < want_items) R >>= 1;
     s.chunk_rows = R;
     s.n_chunks = (N + R - 1) / R;
     s.loc_chunk0 = (N - p->window) / R;

@@ -66,6 +66,22 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsig
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(m0v) : "memory", "m0");
 }
 
+// Four 16-byte DMA instructions under one M0 value: the instruction's immediate offset
+// (0, 1024, 2048, 3072) is added to the global address and to the LDS address alike, so
+// instruction i moves 1 KiB from base + off_i + 1024 i to LDS lds_addr + 1024 i.  The
+// per-lane offsets are passed without the 1024 i term.
+__device__ __forceinline__ void dma_to_lds_x4(const void* base, unsigned off0, unsigned off1, unsigned off2,
+                                              unsigned off3, unsigned lds_addr)
+{
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %5\n\t"
+                 "global_load_lds_dwordx4 %0, %4\n\t"
+                 "global_load_lds_dwordx4 %1, %4 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
+                 "global_load_lds_dwordx4 %3, %4 offset:3072"
+                 ::"v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base), "s"(m0v) : "memory", "m0");
+}
+
 // The value itself, made opaque to the optimiser (stops loop-invariant code motion of what is
 // computed from it).
 __device__ __forceinline__ int opaque_lane(int v)
@@ -759,13 +775,45 @@ __global__ __launch_bounds__(256) void lse_to_base2_kernel(ScoreArgs a)
 //                  tiles are masked, skipped when above the diagonal, and (window rows) also
 //                  added to the local score; a plain loop, one tile at a time;
 //   interior rows  every row sees every key and no row is in the window: one software
-//                  pipeline across tiles and stages, in which the MFMA chain of tile n+1 is
-//                  interleaved with the exp2 / add work of tile n and the next stage's row
-//                  operand and log-sum-exp are fetched from LDS into a second register set.
+//                  pipeline across tiles and stages.  Tiles go in pairs: the MFMA chains of
+//                  the two tiles of a pair alternate (so consecutive matrix instructions never
+//                  depend on each other) and between them the vector ALU turns the two
+//                  accumulators the previous pair left behind into weights; the next stage's
+//                  row operand and log-sum-exp are fetched from LDS into a second register set.
 // ------------------------------------------------------------------------------------
-template <typename T> struct Stream { static constexpr int kSub = 6; static constexpr int kRing = 4; };
+#ifndef EMS_KSUB
+#define EMS_KSUB 8
+#endif
+template <typename T> struct Stream { static constexpr int kSub = EMS_KSUB; static constexpr int kRing = 4; };
 template <> struct Stream<float> { static constexpr int kSub = 2; static constexpr int kRing = 3; };
 constexpr int kStreamRows = 32;            // query rows per stage (one MFMA row tile)
+
+// One 32-row x 32-key tile of the edge loop: weights added into the lane's column sums; the
+// tile may cross the diagonal and may hold last-window rows.
+template <typename T, int D>
+__device__ __forceinline__ void stream_edge_tile(const frag_t (&aq)[Tile<T, D>::kFrags],
+                                                 const frag_t (&bk)[Tile<T, D>::kFrags],
+                                                 const f32x16_t& lse_v, float c, float& glo, float& loc,
+                                                 int row0, int kj, int half, int win0)
+{
+    constexpr int kFrags = Tile<T, D>::kFrags;
+    f32x16_t acc = zero_acc();
+    float p[16];
+#pragma unroll
+    for (int f = 0; f < kFrags; ++f) mma<T>(acc, aq[f], bk[f]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) p[r] = exp2_fast(__builtin_fmaf(acc[r], c, -lse_v[r]));
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        if (row0 + acc_row(r, half) < kj) p[r] = 0.f;
+    glo += sum16(p);
+    if (row0 + 31 >= win0) {                               // wave-uniform
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (row0 + acc_row(r, half) < win0) p[r] = 0.f;
+        loc += sum16(p);
+    }
+}
 
 template <typename T, int D>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void score_pass2_stream_kernel(ScoreArgs a)
@@ -774,7 +822,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     constexpr int kFrags = Tile<T, D>::kFrags;
     constexpr int kEps = 16 / kFrags;                       // accumulator elements handled per MFMA slot
     static_assert(kFrags >= 2 && kFrags <= 16 && 16 % kFrags == 0, "slot schedule needs 2..16 fragments per row");
-    static_assert(kSub >= 2 && kSub % 2 == 0, "tiles alternate between two accumulators across stages");
+    static_assert(kSub >= 2 && kSub % 2 == 0, "tiles are processed in pairs");
+    constexpr int kPairs = kSub / 2;
     constexpr int kRowBytes = Tile<T, D>::kRowBytes;
     constexpr int kCpr = Tile<T, D>::kChunksPerRow;
     constexpr int kStageBytes = kStreamRows * kRowBytes;
@@ -787,6 +836,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     __shared__ __attribute__((aligned(1024))) char lds_q[kRing][kStageBytes];
     __shared__ __attribute__((aligned(256))) float lds_lse[kRing][2 * kStreamRows];   // second half: spare
 
+    const float c = a.scale_log2e;
     const int N = a.seq_len, W = a.window;
     const int G = a.q_heads / a.kv_heads;
     const int n_key_tiles = (N + kKeys - 1) / kKeys;
@@ -843,16 +893,16 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         return (unsigned)row * kRowBytes + (unsigned)(((slot % kCpr) ^ swz_key<T, D>(row)) << 4);
     };
     unsigned dma_off[kKeepDmaOff ? kQInstr : 1];
+    unsigned dma_rel[kKeepDmaOff ? kQInstr : 1];            // the same, relative to the start of the instruction's 1 KiB
     if (kKeepDmaOff) {
 #pragma unroll
-        for (int j = 0; j < kQInstr; ++j) dma_off[j] = dma_src_off(j, lane);
+        for (int j = 0; j < kQInstr; ++j) { dma_off[j] = dma_src_off(j, lane); dma_rel[j] = dma_off[j] - (unsigned)j * 1024u; }
     }
     unsigned frag_off[kFrags];
 #pragma unroll
     for (int f = 0; f < kFrags; ++f)
         frag_off[f] = (unsigned)col * kRowBytes + (unsigned)(((f * 2 + half) ^ swz_key<T, D>(col)) << 4);
 
-    const float c = a.scale_log2e;
     const unsigned lds_q0 = lds_address(&lds_q[0][0]);
     const unsigned lds_l0 = lds_address(&lds_lse[0][0]);
 
@@ -865,9 +915,15 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         if (!kKeepDmaOff) ln = opaque_lane(ln);             // keeps the offsets from being hoisted into registers
         if (kInRange || row + kStreamRows <= N) {
             const char* base = qg + (size_t)row * kRowBytes;
+            if (kKeepDmaOff && kQInstr % 4 == 0) {
 #pragma unroll
-            for (int j = 0; j < kQInstr; ++j)
-                dma_to_lds<16>(base, kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln), dst + j * 1024);
+                for (int j = 0; j < kQInstr; j += 4)
+                    dma_to_lds_x4(base + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst + j * 1024);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kQInstr; ++j)
+                    dma_to_lds<16>(base, kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln), dst + j * 1024);
+            }
         } else {                                            // rows past the end re-read the last row
 #pragma unroll
             for (int j = 0; j < kQInstr; ++j) {
@@ -887,6 +943,20 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         if (later >= 2 && kRing > 3) wait_vmem<2 * kLoads>();
         else if (later >= 1) wait_vmem<kLoads>();
         else wait_vmem<0>();
+    };
+    // LDS -> registers: this lane's operand fragments of a staged row tile, and the 16 values of
+    // the rows' log-sum-exp its accumulator registers stand for
+    auto fetch_rows = [&](int slot, frag_t (&q_out)[kFrags], f32x16_t& l_out) __attribute__((always_inline)) {
+        const char* qs = lds_q[slot];
+        const float* ls = lds_lse[slot];
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f) q_out[f] = *reinterpret_cast<const frag_t*>(qs + frag_off[f]);
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ls + 8 * q4 + 4 * half);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) l_out[4 * q4 + i] = v[i];
+        }
     };
 
     float part[kSub][kEps], loc[kSub];
@@ -913,23 +983,15 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             if (t + kRing - 1 < n_stages)
                 issue((t + kRing - 1) / per_head, row_of(t + kRing - 1), (t + kRing - 1) % kRing, std::false_type{});
             wait_landed(t, min(n_stages - 1, t + kRing - 1));
-            const char* qs = lds_q[t % kRing];
-            const float* ls = lds_lse[t % kRing];
             frag_t aq[kFrags];
-            float lse_r[16];
-#pragma unroll
-            for (int f = 0; f < kFrags; ++f) aq[f] = *reinterpret_cast<const frag_t*>(qs + frag_off[f]);
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ls + 8 * q4 + 4 * half);
-                lse_r[4 * q4 + 0] = v[0]; lse_r[4 * q4 + 1] = v[1]; lse_r[4 * q4 + 2] = v[2]; lse_r[4 * q4 + 3] = v[3];
-            }
+            f32x16_t lse_v;
+            fetch_rows(t % kRing, aq, lse_v);
             const int row0 = row_of(t);
 #pragma unroll
             for (int ks = 0; ks < kSub; ++ks) {
                 const int ks0 = key_base + ks * 32;
                 if (row0 + 31 >= ks0)                        // wave-uniform: not entirely above the diagonal
-                    pass2_tile<T, D, true>(aq, bk[ks], lse_r, c, part[ks][0], loc[ks], row0, ks0 + col, half, win0);
+                    stream_edge_tile<T, D>(aq, bk[ks], lse_v, c, part[ks][0], loc[ks], row0, ks0 + col, half, win0);
                 __builtin_amdgcn_sched_barrier(0);           // one tile's temporaries at a time
             }
             // the slot is re-filled by the DMA issued at the top of the next iteration: the
@@ -947,27 +1009,14 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         const int n_stages = per_head * G;                  // even
 
         frag_t aq[2][kFrags];
-        float lse_r[2][16];
-        f32x16_t acc[2];
-        float xp[kEps];                                     // exponents whose exp2 is still owed
-        auto fetch = [&](int t, auto set_c) __attribute__((always_inline)) {   // LDS -> register set of stage t
-            constexpr int set = decltype(set_c)::value;
-            const char* qs = lds_q[t % kRing];
-            const float* ls = lds_lse[t % kRing];
-#pragma unroll
-            for (int f = 0; f < kFrags; ++f) aq[set][f] = *reinterpret_cast<const frag_t*>(qs + frag_off[f]);
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ls + 8 * q4 + 4 * half);
-                lse_r[set][4 * q4 + 0] = v[0]; lse_r[set][4 * q4 + 1] = v[1];
-                lse_r[set][4 * q4 + 2] = v[2]; lse_r[set][4 * q4 + 3] = v[3];
-            }
-        };
-        // issue cursor: stage number, q-head and first row of the next stage to fetch
-        int u_next = 0, g_next = 0, row_next = e_end;
+        f32x16_t lse_v[2];
+        f32x16_t acc[4];
+        // issue cursor: ring slot, q-head and first row of the next stage to fetch
+        int u_next = 0, slot_next = 0, g_next = 0, row_next = e_end;
         auto issue_next = [&]() __attribute__((always_inline)) {
-            issue(g_next, row_next, u_next % kRing, std::true_type{});
+            issue(g_next, row_next, slot_next, std::true_type{});
             ++u_next;
+            slot_next = slot_next + 1 == kRing ? 0 : slot_next + 1;
             const bool more = u_next < n_stages;            // else: stay on the last stage
             const bool wrap = row_next + kStreamRows >= i_end;
             const int row_adv = wrap ? e_end : row_next + kStreamRows;
@@ -978,72 +1027,87 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 #pragma unroll
         for (int i = 0; i < kRing - 1; ++i) issue_next();
         wait_vmem<(kRing - 2) * kLoads>();
-        fetch(0, std::integral_constant<int, 0>{});
-        // The pipeline starts on a tile that weighs nothing: a zero accumulator under an
-        // infinite log-sum-exp, and owed exponents of -inf.
-        acc[1] = zero_acc();
+        fetch_rows(0, aq[0], lse_v[0]);
+        // Pairs alternate between accumulators {0, 1} and {2, 3}.  The pipeline starts on a pair
+        // that weighs nothing: zero logits under an infinite log-sum-exp.
 #pragma unroll
-        for (int r = 0; r < 16; ++r) lse_r[1][r] = INFINITY;
-#pragma unroll
-        for (int e = 0; e < kEps; ++e) xp[e] = -INFINITY;
+        for (int r = 0; r < 16; ++r) {                      // pair 0 of stage 0 writes {0, 1} and reads {2, 3}
+            acc[2][r] = acc[3][r] = 0.f;
+            lse_v[1][r] = INFINITY;
+        }
 
-        // One stage: tile ks runs its MFMA chain into acc[ks & 1] while the vector ALU turns the
-        // tile before it (acc[1 - (ks & 1)]; for ks = 0 the last tile of the previous stage, whose
-        // rows' log-sum-exp is in the other register set) into weights.  Slot f of a chain does
-        // the exp2 of the elements whose exponents were formed in slot f - 1, so the first read
-        // of an accumulator comes a full slot after the chain that wrote it has ended.
+        // One stage = kPairs rounds.  In round p the chains of tiles 2p and 2p+1 alternate, slot by
+        // slot, and after each MFMA the vector ALU weighs kEps elements of the matching tile of the
+        // previous pair (for p = 0 the last pair of the previous stage, whose rows' log-sum-exp is
+        // in the other register set).  An accumulator is first read two MFMAs and a dozen vector
+        // instructions after the chain that wrote it has ended.
         auto stage = [&](int t, auto set_c) __attribute__((always_inline)) {
             constexpr int set = decltype(set_c)::value;
+#ifdef EMS_FETCH_AT
+            constexpr int kFetchAt = EMS_FETCH_AT;
+#else
+            constexpr int kFetchAt = kPairs - 1;            // late: the DMA has had most of a stage more to land
+#endif
+#ifndef EMS_NO_DMA
             issue_next();                                   // stage t + kRing - 1
+#endif
 #pragma unroll
-            for (int ks = 0; ks < kSub; ++ks) {
-                constexpr int kLast = kFrags - 1;
-                const int ps = (ks + kSub - 1) % kSub;       // key subtile of the tile being weighed
-                const int pps = (ks + kSub - 2) % kSub;      // key subtile the owed exponents belong to
-                f32x16_t& cur = acc[ks & 1];
-                const f32x16_t& prev = acc[1 - (ks & 1)];
-                const float (&pl)[16] = lse_r[ks == 0 ? 1 - set : set];
+            for (int p = 0; p < kPairs; ++p) {
+                constexpr int kOddPairs = kPairs % 2;
+                const int rp = (kOddPairs ? set + p : p) & 1;                 // accumulators this round writes: {2rp, 2rp+1}
+                const int psa = (2 * p + kSub - 2) % kSub;                     // key subtiles of the previous pair
+                f32x16_t& accA = acc[2 * rp];
+                f32x16_t& accB = acc[2 * rp + 1];
+                const f32x16_t& prevA = acc[2 * (1 - rp)];
+                const f32x16_t& prevB = acc[2 * (1 - rp) + 1];
+                const f32x16_t& pl = lse_v[p == 0 ? 1 - set : set];
 #pragma unroll
                 for (int f = 0; f < kFrags; ++f) {
-                    if (f == 0) mma_first<T>(cur, aq[set][0], bk[ks][0]);
-                    else mma<T>(cur, aq[set][f], bk[ks][f]);
-                    if (f == 0) {
+                    if (f == 0) mma_first<T>(accA, aq[set][0], bk[2 * p][0]);
+                    else mma<T>(accA, aq[set][f], bk[2 * p][f]);
 #pragma unroll
-                        for (int e = 0; e < kEps; ++e) part[pps][e] += exp2_fast(xp[e]);
-                        // the previous stage's register set is free from here on; stage t + 1 has
-                        // landed once only the kRing - 2 stages issued after it are in flight
-                        if (ks == 1) {
-                            wait_vmem<(kRing - 2) * kLoads>();
-                            fetch(t + 1, std::integral_constant<int, 1 - set>{});
-                        }
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < kEps; ++e) {
-                            const int r = (f - 1) * kEps + e;
-                            part[ps][e] += exp2_fast(__builtin_fmaf(prev[r], c, -pl[r]));
-                        }
+                    for (int e = 0; e < kEps; ++e) {
+                        const int r = f * kEps + e;
+                        part[psa][e] += exp2_fast(__builtin_fmaf(prevA[r], c, -pl[r]));
                     }
-                    if (f == kLast) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (f == 0) mma_first<T>(accB, aq[set][0], bk[2 * p + 1][0]);
+                    else mma<T>(accB, aq[set][f], bk[2 * p + 1][f]);
 #pragma unroll
-                        for (int e = 0; e < kEps; ++e) {
-                            const int r = kLast * kEps + e;
-                            xp[e] = __builtin_fmaf(prev[r], c, -pl[r]);
-                        }
+                    for (int e = 0; e < kEps; ++e) {
+                        const int r = f * kEps + e;
+                        part[psa + 1][e] += exp2_fast(__builtin_fmaf(prevB[r], c, -pl[r]));
+                    }
+                    // The other register set is free once round 0 has read the previous stage's
+                    // log-sum-exp; stage t + 1 has landed once only the kRing - 2 stages issued
+                    // after it are in flight.
+                    if (kPairs > 1 && p == (kFetchAt < 1 ? 1 : kFetchAt) && f == 0) {
+#ifndef EMS_NO_FETCH
+                        wait_vmem<(kRing - 2) * kLoads>();
+                        fetch_rows((t + 1) % kRing, aq[1 - set], lse_v[1 - set]);
+#endif
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            }
+            if (kPairs == 1) {                              // (validation type) nothing to hide the fetch behind
+                wait_vmem<(kRing - 2) * kLoads>();
+                fetch_rows((t + 1) % kRing, aq[1 - set], lse_v[1 - set]);
             }
         };
         for (int t = 0; t < n_stages; t += 2) {
             stage(t, std::integral_constant<int, 0>{});
             stage(t + 1, std::integral_constant<int, 1>{});
         }
-        // the last tile (key subtile kSub - 1 of the last stage, register set 1) and the owed exponents
+        // the last pair (key subtiles kSub - 2 and kSub - 1 of the last stage, register set 1)
+        {
+            constexpr int rp = ((kPairs % 2 ? 1 + kPairs - 1 : kPairs - 1)) & 1;
 #pragma unroll
-        for (int e = 0; e < kEps; ++e) part[kSub - 2][e] += exp2_fast(xp[e]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            part[kSub - 1][r % kEps] += exp2_fast(__builtin_fmaf(acc[1][r], c, -lse_r[1][r]));
+            for (int r = 0; r < 16; ++r) {
+                part[kSub - 2][r % kEps] += exp2_fast(__builtin_fmaf(acc[2 * rp][r], c, -lse_v[1][r]));
+                part[kSub - 1][r % kEps] += exp2_fast(__builtin_fmaf(acc[2 * rp + 1][r], c, -lse_v[1][r]));
+            }
+        }
         wait_vmem<0>();                                     // no DMA may outlive the wave's LDS
     }
 
@@ -1069,6 +1133,319 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Pass 1, wave-private form.  A work item is ONE wave: it keeps 32 * kSub query rows of one
+// q-head in registers (MFMA B operand, queries -> lanes) and streams the keys of its share of
+// the causal range, 32 at a time, through its own LDS ring (A operand, keys -> accumulator
+// registers): the row sum of a query is a per-lane scalar and there is no workgroup barrier.
+//
+//   online stages    the key stages that touch the diagonal of this wave's queries (masked),
+//                    or, for a key range that has none, its first stage: textbook online
+//                    softmax per tile (running maximum and rescaled sum), one tile at a time.
+//                    They leave every lane a reference exponent m.
+//   interior stages  every key is visible to every query: the software pipeline of the second
+//                    pass (paired MFMA chains, weights of the previous pair in between), with
+//                    the reference m held fixed: sum += exp2(c * S - m).  Any m gives the same
+//                    log-sum-exp m + log2(sum) as long as the sum stays inside the float range,
+//                    i.e. no later exponent exceeds m by ~100: if a sum does leave the range,
+//                    the wave redoes its interior stages with the online form.
+// ------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void score_pass1_stream_kernel(ScoreArgs a)
+{
+    constexpr int kSub = Stream<T>::kSub, kRing = Stream<T>::kRing;
+    constexpr int kFrags = Tile<T, D>::kFrags;
+    constexpr int kEps = 16 / kFrags;
+    static_assert(kFrags >= 2 && kFrags <= 16 && 16 % kFrags == 0, "slot schedule needs 2..16 fragments per row");
+    static_assert(kSub >= 2 && kSub % 2 == 0, "tiles are processed in pairs");
+    constexpr int kPairs = kSub / 2;
+    constexpr int kRowBytes = Tile<T, D>::kRowBytes;
+    constexpr int kCpr = Tile<T, D>::kChunksPerRow;
+    constexpr int kStageBytes = kStreamRows * kRowBytes;
+    constexpr int kLoads = kStageBytes / 1024;              // 16-byte DMA instructions per stage
+    static_assert((kRing - 1) * kLoads < 64, "vmcnt is a 6-bit counter");
+    static_assert(kRing == 3 || kRing == 4, "the waits below are written for rings of 3 or 4 stages");
+    constexpr int kRows = 32 * kSub;                        // query rows per wave
+
+    __shared__ __attribute__((aligned(1024))) char lds_k[kRing][kStageBytes];
+
+    const int N = a.seq_len;
+    const int n_row_tiles = (N + kRows - 1) / kRows;
+    const int G = a.q_heads / a.kv_heads;
+    int bid = xcd_work_item(a.p1_groups, a.p1_per_group);
+    if (bid < 0) return;
+    const int S = a.p1_splits, sp = bid % S; bid /= S;           // this wave's share of the key range
+    const int g = bid % G; bid /= G;
+    const int BKV = a.batch * a.kv_heads;
+    int rt, bkv;                                  // bkv = b * kv_heads + kv
+    if (a.p1_groups == BKV) { rt = n_row_tiles - 1 - (bid % n_row_tiles); bkv = bid / n_row_tiles; }
+    else { bkv = bid % BKV; rt = n_row_tiles - 1 - (bid / BKV); }   // heaviest row tiles first
+    const int b = bkv / a.kv_heads, kvh = bkv % a.kv_heads;
+    const int h = kvh * G + g;
+
+    const T* Q = reinterpret_cast<const T*>(a.q) + ((size_t)(b * a.q_heads + h) * N) * D;
+    const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
+
+    const int lane = threadIdx.x;
+    const int col = lane & 31, half = lane >> 5;
+    const int q_base = rt * kRows;
+    const float c = a.scale_log2e;
+
+    frag_t bq[kSub][kFrags];
+#pragma unroll
+    for (int s = 0; s < kSub; ++s) {
+        const int qi = q_base + s * 32 + col;
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f)
+            bq[s][f] = load_frag_or_zero(Q, (size_t)qi * kRowBytes + f * 32 + half * 16, qi < N);
+    }
+    // the stationary operand lives in the accumulation registers (only the matrix instructions read it)
+#pragma unroll
+    for (int s = 0; s < kSub; ++s)
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f) asm volatile("" : "+a"(bq[s][f]));
+
+    constexpr bool kKeepDmaOff = kLoads <= 8;
+    auto dma_src_off = [&](int j, int ln) __attribute__((always_inline)) {
+        const int slot = j * kWave + ln, row = slot / kCpr;
+        return (unsigned)row * kRowBytes + (unsigned)(((slot % kCpr) ^ swz_key<T, D>(row)) << 4);
+    };
+    unsigned dma_off[kKeepDmaOff ? kLoads : 1];
+    unsigned dma_rel[kKeepDmaOff ? kLoads : 1];
+    if (kKeepDmaOff) {
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) { dma_off[j] = dma_src_off(j, lane); dma_rel[j] = dma_off[j] - (unsigned)j * 1024u; }
+    }
+    unsigned frag_off[kFrags];
+#pragma unroll
+    for (int f = 0; f < kFrags; ++f)
+        frag_off[f] = (unsigned)col * kRowBytes + (unsigned)(((f * 2 + half) ^ swz_key<T, D>(col)) << 4);
+    const unsigned lds_k0 = lds_address(&lds_k[0][0]);
+
+    // DMA of key stage t (keys 32 t ..) into ring slot `slot`
+    auto issue = [&](int t, int slot, auto in_range_c) __attribute__((always_inline)) {
+        constexpr bool kInRange = decltype(in_range_c)::value;   // caller knows 32 t + 32 <= N
+        const int row = t * kStreamRows;
+        const unsigned dst = lds_k0 + slot * kStageBytes;
+        int ln = lane;
+        if (!kKeepDmaOff) ln = opaque_lane(ln);
+        if (kInRange || row + kStreamRows <= N) {
+            const char* base = reinterpret_cast<const char*>(K) + (size_t)row * kRowBytes;
+            if (kKeepDmaOff && kLoads % 4 == 0) {
+#pragma unroll
+                for (int j = 0; j < kLoads; j += 4)
+                    dma_to_lds_x4(base + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst + j * 1024);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kLoads; ++j)
+                    dma_to_lds<16>(base, kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln), dst + j * 1024);
+            }
+        } else {                                            // keys past the end re-read the last key (always masked)
+#pragma unroll
+            for (int j = 0; j < kLoads; ++j) {
+                const int r = (j * kWave + lane) / kCpr;
+                const int over = max(row + r - (N - 1), 0);
+                const unsigned off = kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln);
+                dma_to_lds<16>(K, (unsigned)row * kRowBytes + off - (unsigned)over * kRowBytes, dst + j * 1024);
+            }
+        }
+    };
+    auto wait_landed = [&](int t, int last) __attribute__((always_inline)) {
+        const int later = last - t;
+        if (later >= 2 && kRing > 3) wait_vmem<2 * kLoads>();
+        else if (later >= 1) wait_vmem<kLoads>();
+        else wait_vmem<0>();
+    };
+    auto fetch_keys = [&](int slot, frag_t (&k_out)[kFrags]) __attribute__((always_inline)) {
+        const char* ks = lds_k[slot];
+#pragma unroll
+        for (int f = 0; f < kFrags; ++f) k_out[f] = *reinterpret_cast<const frag_t*>(ks + frag_off[f]);
+    };
+
+    // this wave's key stages: [t0, t1) of the stages a row tile can see; the stages from t_diag on
+    // touch the diagonal
+    const int last_key = min(N, q_base + kRows);                // exclusive
+    const int n_all = (last_key + kStreamRows - 1) / kStreamRows;
+    const int t0 = (int)((long long)n_all * sp / S), t1 = (int)((long long)n_all * (sp + 1) / S);
+    const int t_diag = max(t0, q_base / kStreamRows);
+    const int n_edge = max(t1 - t_diag, 0);
+    // interior stages [t0, min(t1, t_diag)): the first n_lead of them are done in the online form --
+    // one when there is no diagonal stage to take the reference from, one more to make the
+    // pipelined rest even
+    const int n_int_all = max(min(t1, t_diag) - t0, 0);
+    int n_lead = n_edge == 0 && n_int_all > 0 ? 1 : 0;
+    if ((n_int_all - n_lead) & 1) ++n_lead;
+    const int n_int = n_int_all - n_lead;                        // even, >= 0
+
+    float m_run[kSub], l_run[kSub];
+#pragma unroll
+    for (int s = 0; s < kSub; ++s) { m_run[s] = -INFINITY; l_run[s] = 0.f; }
+
+    // Online form over a list of stages: `n_a` stages from `first_a`, then `n_b` from `first_b`.
+    auto online_phase = [&](int first_a, int n_a, int first_b, int n_b) __attribute__((always_inline)) {
+        const int n_stages = n_a + n_b;
+        auto stage_of = [&](int u) __attribute__((always_inline)) { return u < n_a ? first_a + u : first_b + (u - n_a); };
+        for (int u = 0; u < kRing - 1 && u < n_stages; ++u) issue(stage_of(u), u % kRing, std::false_type{});
+        for (int u = 0; u < n_stages; ++u) {
+            if (u + kRing - 1 < n_stages) issue(stage_of(u + kRing - 1), (u + kRing - 1) % kRing, std::false_type{});
+            wait_landed(u, min(n_stages - 1, u + kRing - 1));
+            frag_t ak[kFrags];
+            fetch_keys(u % kRing, ak);
+            const int key0 = stage_of(u) * kStreamRows;
+#pragma unroll
+            for (int s = 0; s < kSub; ++s) {
+                const int qs0 = q_base + s * 32;
+                if (key0 <= qs0 + 31)                        // wave-uniform: not entirely above the diagonal
+                    pass1_tile<T, D, true>(ak, bq[s], m_run[s], l_run[s], c, key0, qs0 + col, half);
+                __builtin_amdgcn_sched_barrier(0);           // one tile's temporaries at a time
+            }
+        }
+        wait_vmem<0>();
+    };
+
+    wait_vmem_all_visible();
+    online_phase(t0, n_lead, t_diag, n_edge);
+
+    if (n_int > 0) {
+        // A lane that has seen no key yet (its half of the diagonal tile lay above the diagonal)
+        // borrows the reference of the other half of the wave, which holds the same queries.
+        float m_fix[kSub], l_save[kSub];
+#pragma unroll
+        for (int s = 0; s < kSub; ++s) {
+            const float m_o = __shfl_xor(m_run[s], 32);
+            m_fix[s] = m_run[s] == -INFINITY ? (m_o == -INFINITY ? 0.f : m_o) : m_run[s];
+            l_save[s] = l_run[s];
+        }
+        const int ti0 = t0 + n_lead;                             // interior stages [ti0, ti0 + n_int)
+
+        frag_t ak[2][kFrags];
+        f32x16_t acc[4];
+        float lsum[kSub][kEps];
+#pragma unroll
+        for (int s = 0; s < kSub; ++s)
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) lsum[s][e] = 0.f;
+
+        int u_next = 0, slot_next = 0;
+        auto issue_next = [&]() __attribute__((always_inline)) {       // past the end: the last stage again, unread
+            issue(ti0 + min(u_next, n_int - 1), slot_next, std::true_type{});
+            ++u_next;
+            slot_next = slot_next + 1 == kRing ? 0 : slot_next + 1;
+        };
+#pragma unroll
+        for (int i = 0; i < kRing - 1; ++i) issue_next();
+        wait_vmem<(kRing - 2) * kLoads>();
+        fetch_keys(0, ak[0]);
+        // the pipeline starts on a pair that weighs nothing: exponents of -inf
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[2][r] = acc[3][r] = -INFINITY;
+
+        // One stage = kPairs rounds; in round p the chains of query subtiles 2p and 2p+1 alternate
+        // and after each MFMA the vector ALU weighs kEps elements of the matching tile of the
+        // previous pair (same structure as the second pass; the exponent's offset is the lane's m).
+        auto stage = [&](int u, auto set_c) __attribute__((always_inline)) {
+            constexpr int set = decltype(set_c)::value;
+            issue_next();                                   // stage u + kRing - 1
+#pragma unroll
+            for (int p = 0; p < kPairs; ++p) {
+                constexpr int kOddPairs = kPairs % 2;
+                const int rp = (kOddPairs ? set + p : p) & 1;
+                const int psa = (2 * p + kSub - 2) % kSub;       // query subtiles of the previous pair
+                f32x16_t& accA = acc[2 * rp];
+                f32x16_t& accB = acc[2 * rp + 1];
+                const f32x16_t& prevA = acc[2 * (1 - rp)];
+                const f32x16_t& prevB = acc[2 * (1 - rp) + 1];
+#pragma unroll
+                for (int f = 0; f < kFrags; ++f) {
+                    if (f == 0) mma_first<T>(accA, ak[set][0], bq[2 * p][0]);
+                    else mma<T>(accA, ak[set][f], bq[2 * p][f]);
+#pragma unroll
+                    for (int e = 0; e < kEps; ++e)
+                        lsum[psa][e] += exp2_fast(__builtin_fmaf(prevA[f * kEps + e], c, -m_fix[psa]));
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (f == 0) mma_first<T>(accB, ak[set][0], bq[2 * p + 1][0]);
+                    else mma<T>(accB, ak[set][f], bq[2 * p + 1][f]);
+#pragma unroll
+                    for (int e = 0; e < kEps; ++e)
+                        lsum[psa + 1][e] += exp2_fast(__builtin_fmaf(prevB[f * kEps + e], c, -m_fix[psa + 1]));
+                    if (kPairs > 1 && p == kPairs - 1 && f == 0) {   // the other register set is free
+                        wait_vmem<(kRing - 2) * kLoads>();
+                        fetch_keys((u + 1) % kRing, ak[1 - set]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (kPairs == 1) {
+                wait_vmem<(kRing - 2) * kLoads>();
+                fetch_keys((u + 1) % kRing, ak[1 - set]);
+            }
+        };
+        for (int u = 0; u < n_int; u += 2) {
+            stage(u, std::integral_constant<int, 0>{});
+            stage(u + 1, std::integral_constant<int, 1>{});
+        }
+        {   // the last pair (query subtiles kSub - 2 and kSub - 1 of the last stage, register set 1)
+            constexpr int rp = ((kPairs % 2 ? 1 + kPairs - 1 : kPairs - 1)) & 1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                lsum[kSub - 2][r % kEps] += exp2_fast(__builtin_fmaf(acc[2 * rp][r], c, -m_fix[kSub - 2]));
+                lsum[kSub - 1][r % kEps] += exp2_fast(__builtin_fmaf(acc[2 * rp + 1][r], c, -m_fix[kSub - 1]));
+            }
+        }
+        wait_vmem<0>();
+
+        // fold the interior sums into the running pair; a sum outside the float range (or NaN)
+        // sends the whole wave back through its interior stages in the online form
+        bool bad = false;
+#pragma unroll
+        for (int s = 0; s < kSub; ++s) {
+            float t = lsum[s][0];
+#pragma unroll
+            for (int e = 1; e < kEps; ++e) t += lsum[s][e];
+            // l_run is relative to m_run (or empty); rebase it to m_fix
+            const float l_old = m_run[s] == -INFINITY ? 0.f : l_run[s];
+            l_run[s] = l_old + t;
+            m_run[s] = m_fix[s];
+            bad |= !(l_run[s] < INFINITY);
+        }
+        if (__any(bad)) {
+#pragma unroll
+            for (int s = 0; s < kSub; ++s) {
+                // back to the state after the first online phase (a lane that had seen a key has a
+                // sum of at least one; an empty sum means the lane had no reference of its own)
+                l_run[s] = l_save[s];
+                m_run[s] = l_save[s] == 0.f ? -INFINITY : m_fix[s];
+            }
+            online_phase(ti0, n_int, 0, 0);
+        }
+    }
+
+    const size_t bh = (size_t)(b * a.q_heads + h);
+    float* lse2 = a.lse2 + bh * a.n_pad;
+    float* lse_nat = a.lse_opt ? a.lse_opt + bh * N : nullptr;
+#pragma unroll
+    for (int s = 0; s < kSub; ++s) {
+        const float m_o = __shfl_xor(m_run[s], 32);
+        const float l_o = __shfl_xor(l_run[s], 32);
+        const float M = fmaxf(m_run[s], m_o);
+        const float Mu = (M == -INFINITY) ? 0.f : M;
+        const float L = l_run[s] * exp2_fast(m_run[s] - Mu) + l_o * exp2_fast(m_o - Mu);
+        const int qi = q_base + s * 32 + col;
+        if (S > 1) {
+            // partial (reference, sum) of this key range; combined by lse_combine_kernel
+            if (half == 0 && qi < a.n_pad) {
+                a.part_m[((size_t)sp * a.batch * a.q_heads + bh) * a.n_pad + qi] = M;
+                a.part_l[((size_t)sp * a.batch * a.q_heads + bh) * a.n_pad + qi] = L;
+            }
+            continue;
+        }
+        const float v = Mu + log2_fast(L);
+        // rows past the end get +inf: the second pass then gives them weight zero
+        if (half == 0 && qi < a.n_pad) lse2[qi] = qi < N ? v : INFINITY;
+        if (half == 0 && qi < N && lse_nat) lse_nat[qi] = v * 0.693147180559945309f;
+    }
+}
+
 template <typename T> static int keys_per_block() { return kWavesPerBlock * 32 * Sub<T>::kSub; }
 
 static bool use_old_pass2() { static const bool v = std::getenv("EMS_P2_OLD") != nullptr; return v; }   // development switch
@@ -1082,10 +1459,11 @@ int score_keys_per_block(int dtype_is_f32)
 template <typename T, int D>
 static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
 {
-    constexpr int kRows = kWavesPerBlock * 32 * Sub<T>::kSub;
+    const bool use_old = use_old_pass2();
+    const int kRows = use_old ? kWavesPerBlock * 32 * Sub<T>::kSub : 32 * Stream<T>::kSub;
     const int BKV = a.batch * a.kv_heads, G = a.q_heads / a.kv_heads;
     const int n_row_tiles = (a.seq_len + kRows - 1) / kRows;
-    // blocks of one (b, kv-head) stream the same K: one group per XCD when there are enough
+    // work items of one (b, kv-head) stream the same K: one group per XCD when there are enough
     // heads to keep all XCDs busy, else groups of the G q-heads of one row tile
     ScoreArgs a1 = a;
     const int S = a.p1_splits < 1 ? 1 : a.p1_splits;
@@ -1093,7 +1471,8 @@ static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
     if (BKV >= kXcds) { a1.p1_groups = BKV; a1.p1_per_group = n_row_tiles * G * S; }
     else { a1.p1_groups = BKV * n_row_tiles; a1.p1_per_group = G * S; }
     const unsigned grid1 = xcd_grid(a1.p1_groups, a1.p1_per_group);
-    hipLaunchKernelGGL((score_pass1_kernel<T, D>), dim3(grid1), dim3(kBlock), 0, st, a1);
+    if (use_old) hipLaunchKernelGGL((score_pass1_kernel<T, D>), dim3(grid1), dim3(kBlock), 0, st, a1);
+    else hipLaunchKernelGGL((score_pass1_stream_kernel<T, D>), dim3(grid1), dim3(kWave), 0, st, a1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
     hipLaunchKernelGGL(lse_combine_kernel, dim3((a.n_pad + 255) / 256, a.batch * a.q_heads), dim3(256), 0, st, a1);
