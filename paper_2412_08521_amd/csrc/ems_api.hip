@@ -4,7 +4,6 @@
 #include "ems_kernels.h"
 
 #include <cmath>
-#include <cstdlib>
 
 namespace {
 
@@ -54,9 +53,10 @@ struct ScorePlan {
     size_t off_lse2, off_part_glo, off_part_loc, off_part_m, off_part_l, total;
 };
 
-// Row chunks of the key-stationary pass: small enough that there are a few thousand
-// (key tile, row chunk) work items to balance over 256 compute units, large enough that
-// the keys a block holds in registers are reused over many rows.
+// Row chunks of the key-stationary pass: small enough that there are tens of thousands of
+// (key tile, row chunk) work items -- one wave each, 1024 waves resident -- so that the last
+// items to finish are a small part of the run, large enough that the keys a wave holds in
+// registers are reused over many rows.
 ScorePlan plan_score(const ems_params* p)
 {
     ScorePlan s{};
@@ -70,11 +70,8 @@ ScorePlan plan_score(const ems_params* p)
         for (int J = 0; J < n_key_tiles; ++J) t += nI - (int)(((long long)J * kpb) / R);
         return t * bkv;
     };
-    const char* old_p2 = std::getenv("EMS_P2_OLD");
     int R = 4096;
-    const char* it_env = std::getenv("EMS_ITEMS");
-    const long long want_items = it_env ? std::atoll(it_env) : (old_p2 ? 2048 : 32768);
-    while (R > 512 && items(R) < want_items) R >>= 1;
+    while (R > 512 && items(R) < 32768) R >>= 1;
     s.chunk_rows = R;
     s.n_chunks = (N + R - 1) / R;
     s.loc_chunk0 = (N - p->window) / R;
@@ -91,7 +88,7 @@ ScorePlan plan_score(const ems_params* p)
     // Pass 1: a row tile's key range is cut into splits while there are too few row tiles to
     // balance the causal triangle over the chip (short sequences); partial (max, sum) pairs
     // are then combined by a small kernel.
-    const int rpb = kpb;                                              // query rows per pass-1 block
+    const int rpb = kpb;                                              // query rows per pass-1 wave
     const long long row_tiles = (long long)p->batch * p->q_heads * ((N + rpb - 1) / rpb);
     s.p1_splits = 1;
     while (s.p1_splits < 8 && row_tiles * s.p1_splits < 2048 && (N + rpb - 1) / rpb >= 2 * s.p1_splits) s.p1_splits *= 2;

@@ -9,24 +9,17 @@
 // Both passes orient the MFMA so that the index being reduced over lives in the
 // accumulator's registers and the index being kept lives in the lanes: reductions are
 // in-register adds plus one exchange between the two half-waves, no atomics anywhere.
+// Both passes run one wave per work item, one wave per SIMD (the whole register file holds
+// the stationary operand), with a private LDS ring for the streamed operand.
 #include "ems_common.h"
 #include "ems_kernels.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace ems {
 
-constexpr int kWavesPerBlock = 4;
-constexpr int kBlock = kWavesPerBlock * kWave;
-// Per element type: 32-wide subtiles of the stationary operand a wave keeps in registers,
-// and rows of the streamed operand staged in LDS per step (sized so that two stages of
-// the widest row stay well inside the static LDS limit).
-template <typename T> struct Sub { static constexpr int kSub = 2; static constexpr int kStageRows = 64; };
-template <> struct Sub<float> { static constexpr int kSub = 1; static constexpr int kStageRows = 32; };
-
 // ---- staging of the streamed operand: global memory -> LDS without passing through
-// registers (global_load_lds_dwordx4), three stages deep.
+// registers (global_load_lds_dwordx4), a ring of stages deep.
 //
 // One instruction moves 64 lanes x 16 bytes into 1 KiB of consecutive LDS; which 16 bytes of
 // global memory a lane fetches is free, so rows are stored unpadded with their 16-byte
@@ -34,22 +27,11 @@ template <> struct Sub<float> { static constexpr int kSub = 1; static constexpr 
 // consecutive rows then hit 16 different bank groups.  Rows past the end of the matrix
 // re-read the last row: callers never let such rows contribute (they are masked by
 // causality or carry an infinite log-sum-exp).
-constexpr int kBuf = 3;   // LDS stages: one being read, two in flight
-
 template <typename T, int D>
 __device__ __forceinline__ int swz_key(int row)
 {
     return Tile<T, D>::kChunksPerRow >= 16 ? (row & 15) : ((row >> 1) & 7);
 }
-
-template <typename T, int D> struct Stage {
-    static constexpr int kRows = Sub<T>::kStageRows;
-    static constexpr int kRowBytes = Tile<T, D>::kRowBytes;
-    static constexpr int kBytes = kRows * kRowBytes;
-    static constexpr int kCpr = Tile<T, D>::kChunksPerRow;
-    static constexpr int kInstrPerWave = kBytes / 1024 / kWavesPerBlock;   // DMA instructions per wave
-    static_assert(kBytes % (1024 * kWavesPerBlock) == 0, "stage must split evenly over the waves");
-};
 
 // One DMA instruction: every lane moves `kBytes` (16 or 4) from base + off (off per lane,
 // base wave-uniform) to LDS byte address lds_addr + lane * kBytes (lds_addr wave-uniform;
@@ -96,58 +78,11 @@ __device__ __forceinline__ unsigned lds_address(const void* p)
     return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-// This lane's byte offsets inside a stage for the wave's DMA instructions: they depend on
-// the lane and the wave only, so they are computed once per kernel.
-template <typename T, int D> struct StageLane {
-    unsigned off[Stage<T, D>::kInstrPerWave];     // row * row bytes + swizzled chunk * 16
-    int row[Stage<T, D>::kInstrPerWave];
-    __device__ __forceinline__ void init()
-    {
-        using S = Stage<T, D>;
-        const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-#pragma unroll
-        for (int j = 0; j < S::kInstrPerWave; ++j) {
-            const int slot = (wave * S::kInstrPerWave + j) * kWave + lane;   // 16-byte slot of the stage
-            row[j] = slot / S::kCpr;
-            const int chunk = (slot % S::kCpr) ^ swz_key<T, D>(row[j]);
-            off[j] = (unsigned)row[j] * (unsigned)S::kRowBytes + (unsigned)chunk * 16u;
-        }
-    }
-};
-
-// Enqueue this wave's share of one stage (rows row0.. of a [n_rows, D] matrix whose byte
-// size is below 4 GiB) into the stage buffer at LDS address `buf_addr`.
-template <typename T, int D>
-__device__ __forceinline__ void stage_issue(const StageLane<T, D>& sl, unsigned buf_addr, const T* base,
-                                            int row0, int n_rows)
-{
-    using S = Stage<T, D>;
-    const int wave = threadIdx.x / kWave;
-    if (row0 + S::kRows <= n_rows) {
-        // whole stage inside the matrix: uniform base, per-lane offsets as they are
-        const char* stage_base = reinterpret_cast<const char*>(base) + (size_t)row0 * S::kRowBytes;
-#pragma unroll
-        for (int j = 0; j < S::kInstrPerWave; ++j)
-            dma_to_lds<16>(stage_base, sl.off[j], buf_addr + (wave * S::kInstrPerWave + j) * 1024);
-    } else {
-#pragma unroll
-        for (int j = 0; j < S::kInstrPerWave; ++j) {
-            const int over = max(row0 + sl.row[j] - (n_rows - 1), 0);      // rows past the end
-            const unsigned off = (unsigned)row0 * (unsigned)S::kRowBytes + sl.off[j] - (unsigned)over * (unsigned)S::kRowBytes;
-            dma_to_lds<16>(base, off, buf_addr + (wave * S::kInstrPerWave + j) * 1024);
-        }
-    }
-}
-
-// Operand fragment `chunk` (16 bytes) of row `row` of a staged tile.
-template <typename T, int D>
-__device__ __forceinline__ frag_t stage_frag(const char* buf, int row, int chunk)
-{
-    return *reinterpret_cast<const frag_t*>(buf + row * Stage<T, D>::kRowBytes + ((chunk ^ swz_key<T, D>(row)) << 4));
-}
-
 // Wait until at most kOutstanding of this wave's vector-memory operations are in flight
-// (they complete in order), leaving the other counters alone.
+// (they complete in order), leaving the other counters alone.  The counts the kernels pass
+// assume that between the DMA of a stage and its wait the wave issues NO other vector-memory
+// instruction -- in particular no scratch (spill) load or store: the build rejects a score
+// kernel whose compiled form uses scratch memory.
 template <int kOutstanding>
 __device__ __forceinline__ void wait_vmem()
 {
@@ -161,15 +96,6 @@ __device__ __forceinline__ void wait_vmem()
 __device__ __forceinline__ void wait_vmem_all_visible()
 {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt left alone
-}
-
-// Workgroup barrier without the memory fence of __syncthreads(): a fence would drain the
-// stages still in flight.  Ordering of the LDS traffic is kept by the explicit waits.
-__device__ __forceinline__ void block_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
 }
 
 // The hardware deals workgroups to the 8 XCDs (each with its own L2) round-robin in launch
@@ -201,13 +127,6 @@ __device__ __forceinline__ f32x16_t zero_acc()
 {
     return f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 }
-
-// ------------------------------------------------------------------------------------
-// Pass 1.  Block = (b, q-head, tile of 4 * 32 * kSub query rows).  Each wave keeps its
-// queries in registers as the MFMA B operand (queries -> lanes) and streams key tiles
-// through LDS as the A operand (keys -> accumulator registers), so the running row
-// maximum and row sum of the online softmax are per-lane scalars.
-// ------------------------------------------------------------------------------------
 
 // One 32-key x 32-query tile of the online softmax.  kMasked tiles may cross the diagonal.
 template <typename T, int D, bool kMasked>
@@ -241,210 +160,6 @@ __device__ __forceinline__ void pass1_tile(const frag_t (&ak)[Tile<T, D>::kFrags
     m_run = m_new;
 }
 
-template <typename T, int D>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_pass1_kernel(ScoreArgs a)
-{
-    constexpr int kSub = Sub<T>::kSub;
-    constexpr int kStageRows = Sub<T>::kStageRows;
-    constexpr int kFrags = Tile<T, D>::kFrags;
-    constexpr int kRowsPerBlock = kWavesPerBlock * 32 * kSub;
-    constexpr int kLoads = Stage<T, D>::kInstrPerWave;       // DMA operations per wave and stage
-
-    __shared__ __attribute__((aligned(1024))) char lds[kBuf][Stage<T, D>::kBytes];
-
-    const int N = a.seq_len;
-    const int n_row_tiles = (N + kRowsPerBlock - 1) / kRowsPerBlock;
-    const int G = a.q_heads / a.kv_heads;
-    int bid = xcd_work_item(a.p1_groups, a.p1_per_group);
-    if (bid < 0) return;
-    const int S = a.p1_splits, sp = bid % S; bid /= S;           // this block's share of the key range
-    const int g = bid % G; bid /= G;
-    const int BKV = a.batch * a.kv_heads;
-    int rt, bkv;                                  // bkv = b * kv_heads + kv
-    if (a.p1_groups == BKV) { rt = n_row_tiles - 1 - (bid % n_row_tiles); bkv = bid / n_row_tiles; }
-    else { bkv = bid % BKV; rt = n_row_tiles - 1 - (bid / BKV); }   // heaviest row tiles first
-    const int b = bkv / a.kv_heads, kvh = bkv % a.kv_heads;
-    const int h = kvh * G + g;
-
-    const T* Q = reinterpret_cast<const T*>(a.q) + ((size_t)(b * a.q_heads + h) * N) * D;
-    const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
-
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int col = lane & 31, half = lane >> 5;
-    const int q_block0 = rt * kRowsPerBlock;
-    const int q0 = q_block0 + wave * 32 * kSub;
-
-    frag_t bq[kSub][kFrags];
-#pragma unroll
-    for (int s = 0; s < kSub; ++s) {
-        const int qi = q0 + s * 32 + col;
-#pragma unroll
-        for (int f = 0; f < kFrags; ++f)
-            bq[s][f] = load_frag_or_zero(Q, (size_t)qi * Tile<T, D>::kRowBytes + f * 32 + half * 16, qi < N);
-    }
-
-    float m_run[kSub], l_run[kSub];
-#pragma unroll
-    for (int s = 0; s < kSub; ++s) { m_run[s] = -INFINITY; l_run[s] = 0.f; }
-
-    // exponents of the tile whose exp2 is still outstanding (they belong to the last query
-    // subtile; -inf contributes nothing)
-    f32x16_t pend;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) pend[r] = -INFINITY;
-    auto flush_pend1 = [&]() __attribute__((always_inline)) {
-        float tot = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { tot += exp2_fast(pend[r]); pend[r] = -INFINITY; }
-        l_run[kSub - 1] += tot;
-    };
-
-    const int last_key = min(N, (rt + 1) * kRowsPerBlock);      // exclusive
-    const int n_all = (last_key + kStageRows - 1) / kStageRows;
-    const int t_begin = (int)((long long)n_all * sp / S), n_tiles = (int)((long long)n_all * (sp + 1) / S);
-    const float c = a.scale_log2e;
-
-    wait_vmem_all_visible();
-    const unsigned lds0 = lds_address(&lds[0][0]);
-    StageLane<T, D> sl;
-    sl.init();
-    if (t_begin < n_tiles) {                                      // block-uniform (a split can be empty)
-        stage_issue<T, D>(sl, lds0 + (t_begin % kBuf) * Stage<T, D>::kBytes, K, t_begin * kStageRows, N);
-        if (t_begin + 1 < n_tiles) {
-            stage_issue<T, D>(sl, lds0 + ((t_begin + 1) % kBuf) * Stage<T, D>::kBytes, K, (t_begin + 1) * kStageRows, N);
-            wait_vmem<kLoads>();
-        } else wait_vmem<0>();
-        block_barrier();
-    }
-
-    for (int t = t_begin; t < n_tiles; ++t) {
-        // the buffer of stage t+2 was last read in iteration t-1, which every wave has left
-        if (t + 2 < n_tiles)
-            stage_issue<T, D>(sl, lds0 + ((t + 2) % kBuf) * Stage<T, D>::kBytes, K, (t + 2) * kStageRows, N);
-        const char* cur = lds[t % kBuf];
-        const int stage_key0 = t * kStageRows;
-        if (stage_key0 + kStageRows - 1 <= q_block0) {
-            // Steady state: every key of the stage is visible to every query of the block.
-            // Software pipeline written out slot by slot: each MFMA of tile t+1 is followed
-            // by a share of tile t's online-softmax work.  The last tile's running maximum
-            // is settled before the barrier; its exponentials (`pend`) are summed under the
-            // first tile of the next stage.
-            constexpr int kKS = kStageRows / 32, kTiles = kKS * kSub, kEps = 16 / kFrags;
-            frag_t ak[kKS][kFrags];
-#pragma unroll
-            for (int ks = 0; ks < kKS; ++ks)
-#pragma unroll
-                for (int f = 0; f < kFrags; ++f)
-                    ak[ks][f] = stage_frag<T, D>(cur, ks * 32 + col, f * 2 + half);
-            f32x16_t acc[2];
-            float pv[kEps], ls[kEps];
-#pragma unroll
-            for (int e = 0; e < kEps; ++e) { pv[e] = 0.f; ls[e] = 0.f; }
-#pragma unroll
-            for (int f = 0; f < kFrags; ++f) {
-                if (f == 0) mma_first<T>(acc[0], ak[0][0], bq[0][0]);
-                else mma<T>(acc[0], ak[0][f], bq[0][f]);
-#pragma unroll
-                for (int e = 0; e < kEps; ++e) ls[e] += pv[e];
-#pragma unroll
-                for (int e = 0; e < kEps; ++e) pv[e] = exp2_fast(pend[f * kEps + e]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            {
-                float tot = 0.f;
-#pragma unroll
-                for (int e = 0; e < kEps; ++e) tot += ls[e] + pv[e];
-                l_run[kSub - 1] += tot;
-            }
-#pragma unroll
-            for (int t = 0; t < kTiles; ++t) {
-                const int s = t % kSub;
-                const f32x16_t& av = acc[t & 1];
-                // running maximum of the row (finite here: no masked element)
-                float t0 = fmaxf(fmaxf(av[0], av[1]), av[2]);
-                float t1 = fmaxf(fmaxf(av[3], av[4]), av[5]);
-                float t2 = fmaxf(fmaxf(av[6], av[7]), av[8]);
-                float t3 = fmaxf(fmaxf(av[9], av[10]), av[11]);
-                float t4 = fmaxf(fmaxf(av[12], av[13]), av[14]);
-                t0 = fmaxf(fmaxf(t0, t1), t2);
-                t3 = fmaxf(fmaxf(t3, t4), av[15]);
-                const float m_new = fmaxf(m_run[s], fmaxf(t0, t3) * c);
-                l_run[s] *= exp2_fast(m_run[s] - m_new);
-                m_run[s] = m_new;
-                if (t + 1 < kTiles) {
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e) { pv[e] = 0.f; ls[e] = 0.f; }
-#pragma unroll
-                    for (int f = 0; f < kFrags; ++f) {
-                        if (f == 0) mma_first<T>(acc[(t + 1) & 1], ak[(t + 1) / kSub][0], bq[(t + 1) % kSub][0]);
-                        else mma<T>(acc[(t + 1) & 1], ak[(t + 1) / kSub][f], bq[(t + 1) % kSub][f]);
-#pragma unroll
-                        for (int e = 0; e < kEps; ++e) ls[e] += pv[e];
-#pragma unroll
-                        for (int e = 0; e < kEps; ++e)
-                            pv[e] = exp2_fast(__builtin_fmaf(av[f * kEps + e], c, -m_new));
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    float tot = 0.f;
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e) tot += ls[e] + pv[e];
-                    l_run[s] += tot;
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) pend[r] = __builtin_fmaf(av[r], c, -m_new);
-                }
-            }
-        } else {
-            // stages that touch the diagonal: skip tiles above it, mask tiles across it
-            flush_pend1();
-#pragma unroll
-            for (int ks = 0; ks < kStageRows / 32; ++ks) {
-                const int key0 = stage_key0 + ks * 32;
-                if (key0 > q0 + 32 * kSub - 1) continue;        // wave-uniform
-                frag_t ak[kFrags];
-#pragma unroll
-                for (int f = 0; f < kFrags; ++f)
-                    ak[f] = stage_frag<T, D>(cur, ks * 32 + col, f * 2 + half);
-#pragma unroll
-                for (int s = 0; s < kSub; ++s) {
-                    const int qs0 = q0 + s * 32;
-                    if (key0 > qs0 + 31) continue;               // wave-uniform
-                    pass1_tile<T, D, true>(ak, bq[s], m_run[s], l_run[s], c, key0, qs0 + col, half);
-                }
-            }
-        }
-        // stage t+1 must have landed before anyone reads it; stage t+2 may stay in flight
-        if (t + 2 < n_tiles) wait_vmem<kLoads>(); else wait_vmem<0>();
-        block_barrier();
-    }
-
-    flush_pend1();
-    const size_t bh = (size_t)(b * a.q_heads + h);
-    float* lse2 = a.lse2 + bh * a.n_pad;
-    float* lse_nat = a.lse_opt ? a.lse_opt + bh * N : nullptr;
-#pragma unroll
-    for (int s = 0; s < kSub; ++s) {
-        const float m_o = __shfl_xor(m_run[s], 32);
-        const float l_o = __shfl_xor(l_run[s], 32);
-        const float M = fmaxf(m_run[s], m_o);
-        const float Mu = (M == -INFINITY) ? 0.f : M;
-        const float L = l_run[s] * exp2_fast(m_run[s] - Mu) + l_o * exp2_fast(m_o - Mu);
-        const int qi = q0 + s * 32 + col;
-        if (S > 1) {
-            // partial (max, sum) of this key range; combined by lse_combine_kernel
-            if (half == 0 && qi < a.n_pad) {
-                a.part_m[((size_t)sp * a.batch * a.q_heads + bh) * a.n_pad + qi] = M;
-                a.part_l[((size_t)sp * a.batch * a.q_heads + bh) * a.n_pad + qi] = L;
-            }
-            continue;
-        }
-        const float v = Mu + log2_fast(L);
-        // rows past the end get +inf: the second pass then gives them weight zero
-        if (half == 0 && qi < a.n_pad) lse2[qi] = qi < N ? v : INFINITY;
-        if (half == 0 && qi < N && lse_nat) lse_nat[qi] = v * 0.693147180559945309f;
-    }
-}
-
 // Combines the partial (max, sum) pairs of pass 1's key-range splits into the row
 // log-sum-exp, in split order.
 __global__ __launch_bounds__(256) void lse_combine_kernel(ScoreArgs a)
@@ -465,269 +180,6 @@ __global__ __launch_bounds__(256) void lse_combine_kernel(ScoreArgs a)
         if (a.lse_opt) a.lse_opt[bh * a.seq_len + i] = v * 0.693147180559945309f;
     }
     a.lse2[bh * a.n_pad + i] = v;
-}
-
-// ------------------------------------------------------------------------------------
-// Pass 2.  Block = (b, kv-head, tile of 4 * 32 * kSub keys, chunk of query rows).  Each
-// wave keeps its keys in registers as the MFMA B operand (keys -> lanes) and streams the
-// query rows of every q-head of the group through LDS as the A operand (rows ->
-// accumulator registers), so a key's column sum is a per-lane scalar.  Row chunks bound
-// the work per block (causal load balance) and let blocks that run together read the same
-// Q rows; their partial sums are added in a fixed order by score_reduce_kernel.
-// ------------------------------------------------------------------------------------
-
-// One 32-row x 32-key tile: weights 2^(c*S - lse2) added into the lane's column sums.
-// kEdge tiles may cross the diagonal and may hold last-window rows.
-template <typename T, int D, bool kEdge>
-__device__ __forceinline__ void pass2_tile(const frag_t (&aq)[Tile<T, D>::kFrags],
-                                           const frag_t (&bk)[Tile<T, D>::kFrags],
-                                           const float (&lse_r)[16], float c,
-                                           float& glo, float& loc,
-                                           int row0, int kj, int half, int win0)
-{
-    f32x16_t acc = zero_acc();
-#pragma unroll
-    for (int f = 0; f < Tile<T, D>::kFrags; ++f) mma<T>(acc, aq[f], bk[f]);
-    float p[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) p[r] = exp2_fast(__builtin_fmaf(acc[r], c, -lse_r[r]));
-    if (kEdge) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-            if (row0 + acc_row(r, half) < kj) p[r] = 0.f;
-    }
-    glo += sum16(p);
-    if (kEdge) {
-        if (row0 + 31 >= win0) {                                 // wave-uniform
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (row0 + acc_row(r, half) < win0) p[r] = 0.f;
-            loc += sum16(p);
-        }
-    }
-}
-
-template <typename T, int D>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_pass2_kernel(ScoreArgs a)
-{
-    constexpr int kSub = Sub<T>::kSub;
-    constexpr int kStageRows = Sub<T>::kStageRows;
-    constexpr int kFrags = Tile<T, D>::kFrags;
-    constexpr int kKeysPerBlock = kWavesPerBlock * 32 * kSub;
-    constexpr int kLoads = Stage<T, D>::kInstrPerWave + 1;   // DMA operations per wave and stage
-
-    __shared__ __attribute__((aligned(1024))) char lds[kBuf][Stage<T, D>::kBytes];
-    // every wave stages its own copy of the rows' log-sum-exp
-    __shared__ __attribute__((aligned(256))) float lds_lse[kBuf][kWavesPerBlock][kStageRows];
-
-    const int N = a.seq_len, W = a.window;
-    const int G = a.q_heads / a.kv_heads;
-    const int n_key_tiles = (N + kKeysPerBlock - 1) / kKeysPerBlock;
-    const int n_chunks = a.n_chunks, R = a.chunk_rows;
-
-    int bid = xcd_work_item(a.batch * a.kv_heads * n_chunks, n_key_tiles);
-    if (bid < 0) return;
-    // groups in heaviest-first order (late row chunks see the most key tiles), heads
-    // innermost, so that the groups an XCD receives add up to the same work
-    const int J = bid % n_key_tiles; bid /= n_key_tiles;
-    const int BKV = a.batch * a.kv_heads;
-    const int bkv = bid % BKV;
-    const int I = n_chunks - 1 - bid / BKV;
-    const int key_base = J * kKeysPerBlock;
-    // rows of this chunk that can see any key of this tile
-    const int r_begin = max(I * R, (key_base / kStageRows) * kStageRows);
-    const int r_end = min((I + 1) * R, N);
-    if (r_begin >= r_end) return;                 // block-uniform: pair above the diagonal
-
-    const int b = bkv / a.kv_heads, kvh = bkv % a.kv_heads;
-    const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
-
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int col = lane & 31, half = lane >> 5;
-    const int k0 = key_base + wave * 32 * kSub;
-
-    frag_t bk[kSub][kFrags];
-#pragma unroll
-    for (int s = 0; s < kSub; ++s) {
-        const int kj = k0 + s * 32 + col;
-#pragma unroll
-        for (int f = 0; f < kFrags; ++f)
-            bk[s][f] = load_frag_or_zero(K, (size_t)kj * Tile<T, D>::kRowBytes + f * 32 + half * 16, kj < N);
-    }
-
-    float glo[kSub], loc[kSub];
-#pragma unroll
-    for (int s = 0; s < kSub; ++s) { glo[s] = 0.f; loc[s] = 0.f; }
-    // steady-state partial column sums (independent add chains) and the exponents of the
-    // tile whose exp2 is still outstanding (-inf contributes nothing)
-    float part[kSub][16 / kFrags];
-#pragma unroll
-    for (int s = 0; s < kSub; ++s)
-#pragma unroll
-        for (int e = 0; e < 16 / kFrags; ++e) part[s][e] = 0.f;
-    f32x16_t pend;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) pend[r] = -INFINITY;
-    auto flush_pend = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { part[kSub - 1][r % (16 / kFrags)] += exp2_fast(pend[r]); pend[r] = -INFINITY; }
-    };
-
-    const int tiles_per_head = (r_end - r_begin + kStageRows - 1) / kStageRows;
-    const int n_tiles = tiles_per_head * G;
-    const float c = a.scale_log2e;
-    const int win0 = N - W;
-
-    auto q_of = [&](int t) __attribute__((always_inline)) {
-        const int g = t / tiles_per_head;
-        return reinterpret_cast<const T*>(a.q) + ((size_t)(b * a.q_heads + kvh * G + g) * N) * D;
-    };
-    auto lse_of = [&](int t) __attribute__((always_inline)) {
-        const int g = t / tiles_per_head;
-        return a.lse2 + (size_t)(b * a.q_heads + kvh * G + g) * a.n_pad;   // padded with +inf
-    };
-    auto row0_of = [&](int t) __attribute__((always_inline)) { return r_begin + (t % tiles_per_head) * kStageRows; };
-    const unsigned lds0 = lds_address(&lds[0][0]);
-    const unsigned lse0 = lds_address(&lds_lse[0][0][0]) + wave * kStageRows * 4;
-    StageLane<T, D> sl;
-    sl.init();
-    auto issue = [&](int t) __attribute__((always_inline)) {
-        stage_issue<T, D>(sl, lds0 + (t % kBuf) * Stage<T, D>::kBytes, q_of(t), row0_of(t), N);
-        if (kStageRows == kWave || lane < kStageRows)
-            dma_to_lds<4>(lse_of(t), (unsigned)(row0_of(t) + lane) * 4u,
-                          lse0 + (t % kBuf) * (kWavesPerBlock * kStageRows * 4));
-    };
-
-    wait_vmem_all_visible();
-    issue(0);
-    if (n_tiles > 1) { issue(1); wait_vmem<kLoads>(); }
-    else wait_vmem<0>();
-    block_barrier();
-
-    for (int t = 0; t < n_tiles; ++t) {
-        // the buffer of stage t+2 was last read in iteration t-1, which every wave has left
-        if (t + 2 < n_tiles) issue(t + 2);
-        const char* cur = lds[t % kBuf];
-        const float* cur_lse = lds_lse[t % kBuf][wave];
-        const int row_tile0 = row0_of(t);
-        // steady state: all rows of the stage are below every key of the block's tile and
-        // above the last window (rows past the end only occur together with window rows)
-        const bool interior = row_tile0 >= key_base + kKeysPerBlock - 1 && row_tile0 + kStageRows <= win0;
-        if (interior) {
-            // Software pipeline over the stage's tiles, written out slot by slot: each MFMA
-            // of tile t+1 is followed by the exp2/add work of a few elements of tile t, so
-            // the matrix pipe and the vector ALU of this wave are busy at the same time.
-            // The last tile's exponents are carried over (`pend`) and finished under the
-            // first tile of the next stage.
-            constexpr int kRS = kStageRows / 32, kTiles = kRS * kSub, kEps = 16 / kFrags;
-            frag_t aq[kRS][kFrags];
-            float lse_r[kRS][16];
-#pragma unroll
-            for (int rs = 0; rs < kRS; ++rs) {
-#pragma unroll
-                for (int f = 0; f < kFrags; ++f)
-                    aq[rs][f] = stage_frag<T, D>(cur, rs * 32 + col, f * 2 + half);
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(cur_lse + rs * 32 + 8 * q4 + 4 * half);
-                    lse_r[rs][4 * q4 + 0] = v[0]; lse_r[rs][4 * q4 + 1] = v[1];
-                    lse_r[rs][4 * q4 + 2] = v[2]; lse_r[rs][4 * q4 + 3] = v[3];
-                }
-            }
-            f32x16_t acc[2];
-            float pv[kEps];
-#pragma unroll
-            for (int e = 0; e < kEps; ++e) pv[e] = 0.f;
-#pragma unroll
-            for (int f = 0; f < kFrags; ++f) {
-                if (f == 0) mma_first<T>(acc[0], aq[0][0], bk[0][0]);
-                else mma<T>(acc[0], aq[0][f], bk[0][f]);
-#pragma unroll
-                for (int e = 0; e < kEps; ++e) part[kSub - 1][e] += pv[e];
-#pragma unroll
-                for (int e = 0; e < kEps; ++e) pv[e] = exp2_fast(pend[f * kEps + e]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int e = 0; e < kEps; ++e) part[kSub - 1][e] += pv[e];
-#pragma unroll
-            for (int t = 0; t < kTiles; ++t) {
-                if (t + 1 < kTiles) {
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e) pv[e] = 0.f;
-#pragma unroll
-                    for (int f = 0; f < kFrags; ++f) {
-                        if (f == 0) mma_first<T>(acc[(t + 1) & 1], aq[(t + 1) / kSub][0], bk[(t + 1) % kSub][0]);
-                        else mma<T>(acc[(t + 1) & 1], aq[(t + 1) / kSub][f], bk[(t + 1) % kSub][f]);
-#pragma unroll
-                        for (int e = 0; e < kEps; ++e) part[t % kSub][e] += pv[e];
-#pragma unroll
-                        for (int e = 0; e < kEps; ++e)
-                            pv[e] = exp2_fast(__builtin_fmaf(acc[t & 1][f * kEps + e], c, -lse_r[t / kSub][f * kEps + e]));
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e) part[t % kSub][e] += pv[e];
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        pend[r] = __builtin_fmaf(acc[t & 1][r], c, -lse_r[t / kSub][r]);
-                }
-            }
-        } else {
-            flush_pend();
-#pragma unroll
-            for (int rs = 0; rs < kStageRows / 32; ++rs) {
-                const int row0 = row_tile0 + rs * 32;
-                if (row0 + 31 < k0 || row0 >= N) continue;       // wave-uniform
-                frag_t aq[kFrags];
-#pragma unroll
-                for (int f = 0; f < kFrags; ++f)
-                    aq[f] = stage_frag<T, D>(cur, rs * 32 + col, f * 2 + half);
-                float lse_r[16];
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(cur_lse + rs * 32 + 8 * q4 + 4 * half);
-                    lse_r[4 * q4 + 0] = v[0]; lse_r[4 * q4 + 1] = v[1];
-                    lse_r[4 * q4 + 2] = v[2]; lse_r[4 * q4 + 3] = v[3];
-                }
-#pragma unroll
-                for (int s = 0; s < kSub; ++s) {
-                    const int ks0 = k0 + s * 32;
-                    if (row0 + 31 < ks0) continue;               // wave-uniform
-                    pass2_tile<T, D, true>(aq, bk[s], lse_r, c, glo[s], loc[s], row0, ks0 + col, half, win0);
-                }
-            }
-        }
-        // stage t+1 must have landed before anyone reads it; stage t+2 may stay in flight
-        if (t + 2 < n_tiles) wait_vmem<kLoads>(); else wait_vmem<0>();
-        block_barrier();
-    }
-
-    flush_pend();
-#pragma unroll
-    for (int s = 0; s < kSub; ++s)
-#pragma unroll
-        for (int e = 0; e < 16 / kFrags; ++e) glo[s] += part[s][e];
-
-    // the two half-waves hold disjoint row subsets of the same keys
-    const int loc_chunk0 = a.loc_chunk0;
-    float* out_glo = a.n_chunks == 1 ? a.s_glo + (size_t)bkv * N
-                                     : a.part_glo + ((size_t)bkv * n_chunks + I) * N;
-    float* out_loc = nullptr;
-    if (a.n_chunks == 1) out_loc = a.s_loc + (size_t)bkv * N;
-    else if (I >= loc_chunk0)
-        out_loc = a.part_loc + ((size_t)bkv * (n_chunks - loc_chunk0) + (I - loc_chunk0)) * N;
-#pragma unroll
-    for (int s = 0; s < kSub; ++s) {
-        const float gsum = glo[s] + __shfl_xor(glo[s], 32);
-        const float lsum = loc[s] + __shfl_xor(loc[s], 32);
-        const int kj = k0 + s * 32 + col;
-        if (half == 0 && kj < N) {
-            out_glo[kj] = gsum;
-            if (out_loc) out_loc[kj] = lsum;
-        }
-    }
 }
 
 // Adds the row-chunk partial sums of pass 2 in ascending chunk order (fixed order, so the
@@ -781,10 +233,9 @@ __global__ __launch_bounds__(256) void lse_to_base2_kernel(ScoreArgs a)
 //                  accumulators the previous pair left behind into weights; the next stage's
 //                  row operand and log-sum-exp are fetched from LDS into a second register set.
 // ------------------------------------------------------------------------------------
-#ifndef EMS_KSUB
-#define EMS_KSUB 8
-#endif
-template <typename T> struct Stream { static constexpr int kSub = EMS_KSUB; static constexpr int kRing = 4; };
+// 32-wide subtiles of the stationary operand per wave (8 x 8 fragments = the 256 accumulation
+// registers in the 16-bit types) and LDS stages in the wave's ring
+template <typename T> struct Stream { static constexpr int kSub = 8; static constexpr int kRing = 4; };
 template <> struct Stream<float> { static constexpr int kSub = 2; static constexpr int kRing = 3; };
 constexpr int kStreamRows = 32;            // query rows per stage (one MFMA row tile)
 
@@ -1043,14 +494,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         // instructions after the chain that wrote it has ended.
         auto stage = [&](int t, auto set_c) __attribute__((always_inline)) {
             constexpr int set = decltype(set_c)::value;
-#ifdef EMS_FETCH_AT
-            constexpr int kFetchAt = EMS_FETCH_AT;
-#else
             constexpr int kFetchAt = kPairs - 1;            // late: the DMA has had most of a stage more to land
-#endif
-#ifndef EMS_NO_DMA
             issue_next();                                   // stage t + kRing - 1
-#endif
 #pragma unroll
             for (int p = 0; p < kPairs; ++p) {
                 constexpr int kOddPairs = kPairs % 2;
@@ -1082,10 +527,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                     // log-sum-exp; stage t + 1 has landed once only the kRing - 2 stages issued
                     // after it are in flight.
                     if (kPairs > 1 && p == (kFetchAt < 1 ? 1 : kFetchAt) && f == 0) {
-#ifndef EMS_NO_FETCH
                         wait_vmem<(kRing - 2) * kLoads>();
                         fetch_rows((t + 1) % kRing, aq[1 - set], lse_v[1 - set]);
-#endif
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1446,21 +889,12 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     }
 }
 
-template <typename T> static int keys_per_block() { return kWavesPerBlock * 32 * Sub<T>::kSub; }
-
-static bool use_old_pass2() { static const bool v = std::getenv("EMS_P2_OLD") != nullptr; return v; }   // development switch
-
-int score_keys_per_block(int dtype_is_f32)
-{
-    if (use_old_pass2()) return dtype_is_f32 ? keys_per_block<float>() : keys_per_block<bf16_t>();
-    return 32 * (dtype_is_f32 ? Stream<float>::kSub : Stream<bf16_t>::kSub);
-}
+int score_keys_per_block(int dtype_is_f32) { return 32 * (dtype_is_f32 ? Stream<float>::kSub : Stream<bf16_t>::kSub); }
 
 template <typename T, int D>
 static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
 {
-    const bool use_old = use_old_pass2();
-    const int kRows = use_old ? kWavesPerBlock * 32 * Sub<T>::kSub : 32 * Stream<T>::kSub;
+    constexpr int kRows = 32 * Stream<T>::kSub;
     const int BKV = a.batch * a.kv_heads, G = a.q_heads / a.kv_heads;
     const int n_row_tiles = (a.seq_len + kRows - 1) / kRows;
     // work items of one (b, kv-head) stream the same K: one group per XCD when there are enough
@@ -1471,8 +905,7 @@ static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
     if (BKV >= kXcds) { a1.p1_groups = BKV; a1.p1_per_group = n_row_tiles * G * S; }
     else { a1.p1_groups = BKV * n_row_tiles; a1.p1_per_group = G * S; }
     const unsigned grid1 = xcd_grid(a1.p1_groups, a1.p1_per_group);
-    if (use_old) hipLaunchKernelGGL((score_pass1_kernel<T, D>), dim3(grid1), dim3(kBlock), 0, st, a1);
-    else hipLaunchKernelGGL((score_pass1_stream_kernel<T, D>), dim3(grid1), dim3(kWave), 0, st, a1);
+    hipLaunchKernelGGL((score_pass1_stream_kernel<T, D>), dim3(grid1), dim3(kWave), 0, st, a1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
     hipLaunchKernelGGL(lse_combine_kernel, dim3((a.n_pad + 255) / 256, a.batch * a.q_heads), dim3(256), 0, st, a1);
@@ -1482,7 +915,7 @@ static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
 template <typename T, int D>
 static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
 {
-    constexpr int kKeys = kWavesPerBlock * 32 * Sub<T>::kSub;
+    constexpr int kKeys = 32 * Stream<T>::kSub;
     const int BKV = a.batch * a.kv_heads;
     const int n_key_tiles = (a.seq_len + kKeys - 1) / kKeys;
     if (a.lse_in_nat) {
@@ -1490,22 +923,13 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
         hipLaunchKernelGGL(lse_to_base2_kernel, g, dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     }
-    const bool use_old = use_old_pass2();
-    hipError_t e;
-    if (use_old) {
-        const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_key_tiles);
-        hipLaunchKernelGGL((score_pass2_kernel<T, D>), dim3(grid2), dim3(kBlock), 0, st, a);
-        e = hipGetLastError();
-    } else {
-        const int n_tiles_w = (a.seq_len + 32 * Stream<T>::kSub - 1) / (32 * Stream<T>::kSub);
-        const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_tiles_w);
-        hipLaunchKernelGGL((score_pass2_stream_kernel<T, D>), dim3(grid2), dim3(kWave), 0, st, a);
-        e = hipGetLastError();
-    }
+    const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_key_tiles);
+    hipLaunchKernelGGL((score_pass2_stream_kernel<T, D>), dim3(grid2), dim3(kWave), 0, st, a);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
         dim3 g((a.seq_len + 255) / 256, BKV);
-        hipLaunchKernelGGL(score_reduce_kernel, g, dim3(256), 0, st, a, use_old ? kKeys : 32 * Stream<T>::kSub);
+        hipLaunchKernelGGL(score_reduce_kernel, g, dim3(256), 0, st, a, kKeys);
         e = hipGetLastError();
     }
     return e;
