@@ -69,3 +69,48 @@ def check_band(idx_imp, idx_tbm, score, n_cand, tol):
 def is_sorted_unique(a):
     a = np.asarray(a)
     return bool((np.diff(a) > 0).all())
+
+
+def assert_dest_valid(got_dest, ref_dest, kf, imp, tbm, tau, budget, vf=None, tol=2e-5, what="tbm_dest"):
+    """Destinations may differ from the oracle's only where the decision is inside float32 noise:
+    every differing token must have its two best similarities within `tol` of each other (the
+    arg-max could go either way) or its best similarity within `tol` of tau (merge or evict
+    could go either way).  The similarities are recomputed here in float64 from the inputs:
+    key cosine, or the product of key and value cosines when `vf` is given.  Returns the number
+    of differing tokens."""
+    got_dest, ref_dest = np.asarray(got_dest), np.asarray(ref_dest)
+    differ = got_dest != ref_dest
+    for bb, h, i in zip(*np.nonzero(differ)):
+        def unit(x):
+            x = x.astype(np.float64)
+            n = np.linalg.norm(x, axis=-1, keepdims=True)
+            return np.where(n > 0, x / np.where(n > 0, n, 1), 0.0)
+        sims = unit(kf[bb, h, imp[bb, h]]) @ unit(kf[bb, h, tbm[bb, h, i]])
+        if vf is not None:
+            sims = sims * (unit(vf[bb, h, imp[bb, h]]) @ unit(vf[bb, h, tbm[bb, h, i]]))
+        order = np.argsort(sims)
+        best, second = sims[order[-1]], sims[order[-2]] if len(order) > 1 else -np.inf
+        near_tie = best - second < tol
+        near_tau = abs(best - tau) < tol
+        g, r = int(got_dest[bb, h, i]), int(ref_dest[bb, h, i])
+        assert near_tie or near_tau, f"{what}[{bb},{h},{i}]: GPU {g} oracle {r}, best {best} second {second} tau {tau}"
+        # and the GPU's own choice must be one of the valid ones
+        if g == budget:
+            assert near_tau and best <= tau + tol, f"{what}[{bb},{h},{i}]: evicted at similarity {best} > tau {tau}"
+        else:
+            assert sims[g] >= best - tol and sims[g] > tau - tol, \
+                f"{what}[{bb},{h},{i}]: slot {g} has similarity {sims[g]}, best is {best}, tau {tau}"
+    return int(differ.sum())
+
+
+def assert_sparsity_count_valid(n_k, s_glo, s_loc, zeta, tol=2e-5):
+    """Eq. 3 count of one head: k tokens must reach zeta of the total and k - 1 must not, both
+    within float32 noise of the threshold (scores = Eq. 2 output, recomputed here in float64)."""
+    g, l = np.asarray(s_glo, np.float64), np.asarray(s_loc, np.float64)
+    c = l.sum() / g.sum()
+    s = np.sort(np.maximum(g * c, l))[::-1]
+    cs, thr = np.cumsum(s), zeta * s.sum()
+    k = int(n_k)
+    assert 1 <= k <= len(s)
+    assert cs[k - 1] >= thr * (1 - tol), (k, cs[k - 1], thr)
+    assert k == 1 or cs[k - 2] < thr * (1 + tol), (k, cs[k - 2], thr)

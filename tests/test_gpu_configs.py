@@ -10,7 +10,8 @@ import torch
 import ems_inputs
 from oracle import ems_ref
 from paper_2412_08521_amd import binding as B
-from gpu_util import RTOL, RTOL_MERGE, assert_rel, check_band, dev_tensor, ref_params
+from gpu_util import (RTOL, RTOL_MERGE, assert_dest_valid, assert_rel, assert_sparsity_count_valid, check_band,
+                      dev_tensor, ref_params)
 
 pytestmark = pytest.mark.gpu
 
@@ -82,8 +83,9 @@ def _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out,
     ref = ems_ref.evict_merge(rp, kf, vf, imp_n, tbm_n)
     dest = out["tbm_dest"].cpu().numpy()
     np.testing.assert_allclose(out["tbm_sim"].cpu().numpy(), ref["tbm_sim"], rtol=0, atol=5e-6)
-    margin_ok = dest == ref["tbm_dest"]
-    assert margin_ok.mean() > 0.995, margin_ok.mean()
+    # a destination may differ from the oracle's only where the decision is inside float32 noise
+    n_diff = assert_dest_valid(dest, ref["tbm_dest"], kf, imp_n, tbm_n, p.tau, p.budget)
+    assert n_diff <= max(1, dest.size // 200), n_diff
     k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge(rp, kf, vf, imp_n, tbm_n, dest)
     np.testing.assert_array_equal(out["kept_pos"].cpu().numpy(), kept_ref)
     np.testing.assert_array_equal(out["slot_count"].cpu().numpy(), cnt_ref)
@@ -127,7 +129,9 @@ def _check_follow_up_calls(p, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out
     var = _host(B.ems_evict_merge_variant(p, B.EMS_SIM_KEY_VALUE, k, v, pooled, imp, tbm))
     d_ref, s_ref, n_ref = ems_ref.dest_sim(rp, 2, kf, vf, imp_n, tbm_n)
     np.testing.assert_allclose(var["tbm_sim"], s_ref, rtol=0, atol=1e-5)
-    assert (var["tbm_dest"] == d_ref).mean() > 0.995
+    n_diff = assert_dest_valid(var["tbm_dest"], d_ref, kf, imp_n, tbm_n, p.tau, p.budget, vf=vf, tol=4e-5,
+                               what="key x value tbm_dest")
+    assert n_diff <= max(1, d_ref.size // 200), n_diff
     k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge_weighted(rp, kf, vf, pooled.cpu().numpy(), imp_n, tbm_n,
                                                              var["tbm_dest"])
     np.testing.assert_array_equal(var["slot_count"], cnt_ref)
@@ -137,6 +141,10 @@ def _check_follow_up_calls(p, w, host, k, v, s_glo, s_loc, imp, tbm, pooled, out
     rate, nk = B.ems_sparsity_rate(p, 0.9, s_glo, s_loc)
     o_rate, o_nk = ems_ref.sparsity(rp, 0.9, s_glo.cpu().numpy(), s_loc.cpu().numpy())
     assert np.abs(nk.cpu().numpy() - o_nk).max() <= max(2, w.seq_len // 2000), (nk, o_nk)
+    g_n, l_n, nk_n = s_glo.cpu().numpy(), s_loc.cpu().numpy(), nk.cpu().numpy()
+    for b_ in range(w.batch):                              # both sides of the threshold, every head
+        for h_ in range(w.kv_heads):
+            assert_sparsity_count_valid(nk_n[b_, h_], g_n[b_, h_], l_n[b_, h_], 0.9)
     red, best = B.ems_redundancy_rate(p, k, v)
     tokens = np.array([0, 1, 31, 32, 1000, w.seq_len // 2 + 17, w.seq_len - 1], np.int32)
     o_best = ems_ref.redundancy_at(rp, kf, vf, tokens)
@@ -245,14 +253,14 @@ def test_config5_extreme_128k_two_layers():
         s_glo, s_loc, imp, tbm, pooled, out = _run_chain(p, q, k, v)
         _check_properties_all_units(p, w, host, s_glo, s_loc, imp, tbm, pooled, out, B.EMS_BF16)
         if layer == 0:
-            # one q-head against its kv-head as a problem of its own, full length, vs the oracle
-            p1 = B.EmsParams(1, 1, 1, w.head_dim, w.seq_len, w.window)
-            g1, l1 = B.ems_global_local_score(p1, q[:, 9:10].contiguous(), k[:, 2:3].contiguous())
-            rp = ems_ref.RefParams(1, 1, 1, w.head_dim, w.seq_len, w.window)
-            o_glo, o_loc = ems_ref.score(rp, host[0].f32("q")[:, 9:10], host[0].f32("k")[:, 2:3])
-            e1 = assert_rel(g1.cpu().numpy(), o_glo, RTOL[B.EMS_BF16], "s_glo head 9")
-            e2 = assert_rel(l1.cpu().numpy(), o_loc, RTOL[B.EMS_BF16], "s_loc head 9")
-            _log(f"  q-head 9 alone: rel err glo {e1:.2e} loc {e2:.2e}")
+            # one whole (batch, kv-head) unit of the benchmark launch itself -- the group sum over
+            # its 4 q-heads, all row chunks and their reduction -- element by element at full length
+            o_glo, o_loc = _check_unit_against_oracle(p, w, host[0], 0, 2, s_glo, s_loc, RTOL[B.EMS_BF16])
+            rp1 = ems_ref.RefParams(1, 1, 1, w.head_dim, w.seq_len, w.window, budget=w.budget,
+                                    merge_ratio=w.merge_ratio, pool_kernel=w.pool_kernel)
+            o_pooled, _, _ = ems_ref.select(rp1, o_glo[None, None], o_loc[None, None])
+            check_band(imp[0, 2].cpu().numpy(), tbm[0, 2].cpu().numpy(), o_pooled[0, 0],
+                       w.seq_len - w.window, RTOL[B.EMS_BF16])
             p2 = _params(w, 0.15)
             out2 = B.ems_evict_merge(p2, k, v, imp, tbm)
             dest, _ = _check_properties_all_units(p2, w, host, s_glo, s_loc, imp, tbm, pooled, out2,

@@ -7,7 +7,8 @@ import torch
 import ems_inputs
 from oracle import ems_ref
 from paper_2412_08521_amd import binding as B
-from gpu_util import RTOL, RTOL_MERGE, assert_rel, check_band, dev_tensor, is_sorted_unique, ref_params
+from gpu_util import (RTOL, RTOL_MERGE, assert_dest_valid, assert_rel, check_band, dev_tensor, is_sorted_unique,
+                      ref_params)
 
 pytestmark = pytest.mark.gpu
 
@@ -198,17 +199,8 @@ def test_evict_merge_matches_oracle(shape, tau, mode):
     # destinations: equal except where the decision is inside float32 noise
     np.testing.assert_allclose(out["tbm_sim"], ref["tbm_sim"], rtol=0, atol=5e-6)
     np.testing.assert_allclose(out["k_norm"], ref["k_norm"], rtol=1e-6)
-    differ = out["tbm_dest"] != ref["tbm_dest"]
-    if differ.any():
-        for bb, h, i in zip(*np.nonzero(differ)):
-            kk = kf[bb, h].astype(np.float64)
-            u = kk / np.linalg.norm(kk, axis=1, keepdims=True)
-            sims = u[imp[bb, h]] @ u[tbm[bb, h, i]]
-            top2 = np.sort(sims)[-2:]
-            near_tie = top2[1] - top2[0] < 2e-5
-            near_tau = abs(top2[1] - tau) < 2e-5
-            assert near_tie or near_tau, (bb, h, i, top2, tau)
-    assert differ.mean() < 0.01
+    n_diff = assert_dest_valid(out["tbm_dest"], ref["tbm_dest"], kf, imp, tbm, tau, nb)
+    assert n_diff < 0.01 * ref["tbm_dest"].size
     # stage isolation: the oracle's average for the GPU's own destinations
     k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge(rp, kf, vf, imp, tbm, out["tbm_dest"])
     np.testing.assert_array_equal(out["kept_pos"], kept_ref)
@@ -286,8 +278,8 @@ def test_tiny_config_end_to_end(mode):
         np.testing.assert_array_equal(imp_n, x_imp)
         np.testing.assert_array_equal(tbm_n, x_tbm)
         ref = ems_ref.evict_merge(rp, kf, vf, imp_n, tbm_n)
-        same = out["tbm_dest"].cpu().numpy() == ref["tbm_dest"]
-        assert same.mean() > 0.99
+        n_diff = assert_dest_valid(out["tbm_dest"].cpu().numpy(), ref["tbm_dest"], kf, imp_n, tbm_n, tau, w.budget)
+        assert n_diff <= max(1, ref["tbm_dest"].size // 100)
         k_ref, v_ref, kept_ref, cnt_ref = ems_ref.merge(rp, kf, vf, imp_n, tbm_n,
                                                         out["tbm_dest"].cpu().numpy())
         np.testing.assert_array_equal(out["slot_count"].cpu().numpy(), cnt_ref)
