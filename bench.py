@@ -36,6 +36,10 @@ def main():
     ap.add_argument("--f32", action="store_true", help="validation mode (f32 MFMA)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=1,
+                    help="compress this many layers one after the other, each with its own seeded "
+                         "inputs (the 128K workload is stated on 32): reports the per-layer median "
+                         "and the total next to the headline figures, which stay those of --layer")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the timings of the entry points outside the headline step "
                          "(expansion, merge variants, decode-time update)")
@@ -152,31 +156,41 @@ def main():
         import re
         m = re.search(r"hbm_bytes_per_launch:\s*([0-9.eE+]+)", open(tpath).read())
         traffic = float(m.group(1)) if m else None
-    roofline = {"bound": "mfma", "kernel": "score_pass2_kernel", "achieved": round(achieved, 2),
+    roofline = {"bound": "mfma", "kernel": "score_pass2_stream_kernel", "achieved": round(achieved, 2),
                 "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": traffic, "flops_per_launch": flops_pass,
+                "traffic": traffic,
+                "traffic_source": (f"profiles/score_pass2_{w.name}.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                   "runs of this command, scaled by a plain copy; not measured by this process"
+                                   if traffic is not None else None),
+                "flops_per_launch": flops_pass,
                 "ms_per_launch": round(ms_pass2, 4)}
-    pass1 = {"kernel": "score_pass1_kernel", "achieved": round(flops_pass / (ms_pass1 * 1e-3) / 1e12, 2),
+    pass1 = {"kernel": "score_pass1_stream_kernel", "achieved": round(flops_pass / (ms_pass1 * 1e-3) / 1e12, 2),
              "unit": "TFLOP/s", "frac": round(flops_pass / (ms_pass1 * 1e-3) / 1e12 / peak, 4),
              "ms_per_launch": round(ms_pass1, 4)}
 
-    # ---- the machine's own ceilings in the same process: a loop of independent bf16 MFMAs
-    # (16 waves per compute unit) and a plain 16-byte vector copy of Q
+    # ---- the machine's own ceilings in the same process (bench-only library): a loop of bf16
+    # MFMAs, 16 waves per compute unit, on constant operands and on random ones (random data
+    # toggles far more logic: the power limit then sets a lower clock, and that is the ceiling
+    # real inputs see), and a plain 16-byte vector copy of Q
+    from paper_2412_08521_amd import bench_probe
     sink = torch.empty(1024 * 256, dtype=torch.float32, device="cuda")
-    B.ems_probe_mfma(1024, 2000, sink)
+    ops = torch.randn(bench_probe.OPERAND_BYTES // 2, device="cuda").to(torch.bfloat16)
+    bench_probe.probe_mfma(1024, 200, sink)
     torch.cuda.synchronize()
-    probe_flops = 1024 * 4 * 20000 * 4 * 32768
-    ms_mfma = timed(lambda: B.ems_probe_mfma(1024, 20000, sink), 3)
+    probe_flops = 1024 * 4 * 2500 * 32 * 32768
+    ms_mfma_const = timed(lambda: bench_probe.probe_mfma(1024, 2500, sink), 3)
+    ms_mfma_rand = timed(lambda: bench_probe.probe_mfma(1024, 2500, sink, operands=ops), 3)
     q_copy = torch.empty_like(q)
-    B.ems_probe_copy(q, q_copy)
-    ms_copy = timed(lambda: B.ems_probe_copy(q, q_copy), 5)
+    bench_probe.probe_copy(q, q_copy)
+    ms_copy = timed(lambda: bench_probe.probe_copy(q, q_copy), 5)
     copy_bytes = 2 * q.numel() * q.element_size()
     del q_copy
-    ceilings = {"mfma_bf16_tflops": round(probe_flops / (ms_mfma * 1e-3) / 1e12, 1),
+    ceilings = {"mfma_bf16_tflops_constant_operands": round(probe_flops / (ms_mfma_const * 1e-3) / 1e12, 1),
+                "mfma_bf16_tflops_random_operands": round(probe_flops / (ms_mfma_rand * 1e-3) / 1e12, 1),
                 "copy_gbps": round(copy_bytes / (ms_copy * 1e-3) / 1e9, 1)}
     log(f"measured ceilings: {ceilings}")
     if not args.f32:
-        roofline["frac_of_measured_ceiling"] = round(achieved / ceilings["mfma_bf16_tflops"], 4)
+        roofline["frac_of_measured_ceiling"] = round(achieved / ceilings["mfma_bf16_tflops_random_operands"], 4)
 
     tokens = w.batch * w.seq_len
     result = {
@@ -197,6 +211,12 @@ def main():
                             "value": round(tokens / ((ms_pass2 + stages["select"] + stages["evict_merge"]) * 1e-3), 1),
                             "unit": "tokens/s"},
     }
+
+    # ---- several layers one after the other, each with its own seeded inputs
+    if args.layers > 1:
+        result["layers"] = run_layers(args, p, w, B, ems_inputs, torch, np, q, k, v, step,
+                                      s_glo, s_loc, imp, tbm, outs, n_imp, n_tbm)
+        log(f"layers: {result['layers']}")
 
     # ---- entry points outside the headline step, same shapes, reported on their own
     if not args.no_extras:
@@ -230,6 +250,52 @@ def main():
         log(f"cpu baseline: score {t_score:.2f}s rest {t_rest:.3f}s")
 
     print(json.dumps(result), flush=True)
+
+
+def run_layers(args, p, w, B, ems_inputs, torch, np, q, k, v, step, s_glo, s_loc, imp, tbm, outs, n_imp, n_tbm):
+    """One timed step per layer (HIP events), inputs of the layer generated on the host and moved
+    to HBM before its timed region; afterwards, outside the timed region, the properties that hold
+    at any size are asserted on the layer's outputs."""
+    mode_f32 = p.dtype == B.EMS_F32
+    G = w.q_heads // w.kv_heads
+    per_layer = []
+    for layer in range(args.layers):
+        for b in range(w.batch):
+            inp = ems_inputs.generate(w, layer=layer, batch_slice=slice(b, b + 1))
+            for name, dst in (("q", q), ("k", k), ("v", v)):
+                bits = getattr(inp, name)
+                if mode_f32:
+                    dst[b].copy_(torch.from_numpy(ems_inputs.bf16_bits_to_f32(bits[0])))
+                else:
+                    dst[b].copy_(torch.from_numpy(bits[0].view(np.int16)).view(torch.bfloat16))
+            del inp
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        step()
+        e1.record()
+        torch.cuda.synchronize()
+        per_layer.append(e0.elapsed_time(e1))
+        # every causal softmax row sums to one; index sets are sorted, disjoint, in range; every
+        # head emits budget rows that account for all N_imp + N_tbm tokens
+        gs, ls = s_glo.double().sum(-1), s_loc.double().sum(-1)
+        assert ((gs - G * w.seq_len).abs() <= 2e-4 * G * w.seq_len).all(), f"layer {layer}: s_glo row sums"
+        assert ((ls - G * w.window).abs() <= 2e-4 * G * w.window).all(), f"layer {layer}: s_loc row sums"
+        for idx, n in ((imp, n_imp), (tbm, n_tbm)):
+            if n > 1:
+                assert (idx[..., 1:] > idx[..., :-1]).all(), f"layer {layer}: index set not ascending"
+            if n:
+                assert int(idx.min()) >= 0 and int(idx.max()) < w.seq_len - w.window
+        both = torch.cat([imp, tbm], -1).sort(-1).values
+        assert (both[..., 1:] != both[..., :-1]).all(), f"layer {layer}: index sets overlap"
+        assert (outs["slot_count"].sum(-1) == n_imp + n_tbm).all(), f"layer {layer}: slot counts"
+        assert torch.isfinite(outs["k_out"].float()).all() and torch.isfinite(outs["v_out"].float()).all()
+        log(f"layer {layer}: {per_layer[-1]:.3f} ms, invariants ok")
+    total = float(sum(per_layer))
+    return {"n": args.layers, "ms_per_layer_median": round(float(np.median(per_layer)), 4),
+            "ms_per_layer_min": round(min(per_layer), 4), "ms_per_layer_max": round(max(per_layer), 4),
+            "ms_total": round(total, 3),
+            "tokens_per_s_over_all_layers": round(w.batch * w.seq_len * args.layers / (total * 1e-3), 1)}
 
 
 def time_extras(args, p, w, B, torch, timed, k, v, s_glo, s_loc, imp, tbm, merged, ws_select, ws_merge):

@@ -31,7 +31,7 @@ EXPORTS = ("ems_version", "ems_strerror", "ems_partition_sizes", "ems_workspace_
            "ems_global_local_score", "ems_attention_lse", "ems_global_local_score_from_lse",
            "ems_select", "ems_evict_merge", "ems_evict_merge_variant", "ems_expand",
            "ems_decode_workspace_bytes", "ems_decode_init", "ems_decode_step",
-           "ems_sparsity_rate", "ems_redundancy_rate", "ems_probe_mfma", "ems_probe_copy")
+           "ems_sparsity_rate", "ems_redundancy_rate")
 
 
 class ems_params(C.Structure):
@@ -105,8 +105,6 @@ def lib():
         l.ems_expand.argtypes = [P] + [C.c_void_p] * 10
         l.ems_sparsity_rate.argtypes = [P, C.c_float] + [C.c_void_p] * 5
         l.ems_redundancy_rate.argtypes = [P] + [C.c_void_p] * 5
-        l.ems_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
-        l.ems_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         S = C.POINTER(ems_decode_state)
         l.ems_decode_workspace_bytes.argtypes = [P, C.POINTER(C.c_size_t)]
         l.ems_decode_init.argtypes = [P] + [C.c_void_p] * 7 + [S, C.c_void_p]
@@ -457,23 +455,3 @@ def ems_redundancy_rate(p: EmsParams, k, v):
     if rc != EMS_OK:
         raise EmsError(rc, "ems_redundancy_rate")
     return rate, best
-
-
-def ems_probe_mfma(blocks: int, iters: int, sink):
-    """Enqueue the MFMA ceiling kernel; returns the flops it performs."""
-    _check_tensor(sink, (blocks * 256,), torch.float32, "sink")
-    rc = lib().ems_probe_mfma(int(blocks), int(iters), _ptr(sink), _stream())
-    if rc != EMS_OK:
-        raise EmsError(rc, "ems_probe_mfma")
-    return blocks * 4 * iters * 4 * 32768
-
-
-def ems_probe_copy(src, dst):
-    """Enqueue the copy ceiling kernel; returns the bytes it moves (read + written)."""
-    nbytes = src.numel() * src.element_size()
-    if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
-        raise ValueError("src and dst must be device tensors of the same size")
-    rc = lib().ems_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream())
-    if rc != EMS_OK:
-        raise EmsError(rc, "ems_probe_copy")
-    return 2 * nbytes

@@ -13,9 +13,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 OBJ_DIR = os.path.join(_HERE, "_build")
 LIB = os.path.join(_HERE, "libems_hip.so")
-SOURCES = ["ems_api.hip", "score.hip", "select.hip", "merge.hip", "decode.hip", "stats.hip", "probe.hip"]
-HEADERS = ["ems_common.h", "ems_kernels.h", "ems_rows.h", os.path.join("..", "..", "include", "ems.h"),
-           os.path.join("..", "..", "include", "ems_probe.h")]
+SOURCES = ["ems_api.hip", "score.hip", "select.hip", "merge.hip", "decode.hip", "stats.hip"]
+HEADERS = ["ems_common.h", "ems_kernels.h", "ems_rows.h", os.path.join("..", "..", "include", "ems.h")]
+# the benchmark's ceiling measurements: a library of their own, outside the product's interface
+PROBE_DIR = os.path.join(_HERE, "bench_probe")
+PROBE_LIB = os.path.join(_HERE, "libems_probe.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -97,6 +99,13 @@ def build(force: bool = False, verbose: bool = False) -> str:
         if r.returncode != 0:
             raise RuntimeError(f"link failed:\n{r.stderr}")
         os.replace(LIB + ".tmp", LIB)
+    probe_src = os.path.join(PROBE_DIR, "probe.hip")
+    if force or _stale(PROBE_LIB, [probe_src, os.path.join(PROBE_DIR, "ems_probe.h")] + hdrs):
+        cmd = [HIPCC] + FLAGS + ["-shared", probe_src, "-o", PROBE_LIB + ".tmp"]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on probe.hip:\n{r.stderr}")
+        os.replace(PROBE_LIB + ".tmp", PROBE_LIB)
     return LIB
 
 

@@ -101,11 +101,26 @@ ScorePlan plan_score(const ems_params* p)
     return s;
 }
 
-size_t select_ws_bytes(const ems_params* p)
+struct SelectPlan { size_t off_pooled, off_ckey, off_cpos, off_hist, off_sums, off_count, off_info, total; };
+
+SelectPlan plan_select(const ems_params* p)
 {
-    // ranking keys, and (used by the long-sequence kernel) the Eq. 2 vector before pooling
-    return 2 * align_up(sizeof(float) * (size_t)p->batch * p->kv_heads * p->seq_len);
+    SelectPlan s{};
+    const size_t bkv = (size_t)p->batch * p->kv_heads, N = (size_t)p->seq_len;
+    const size_t chunks = (size_t)ems::select_chunks(p->seq_len);
+    size_t off = 0;
+    s.off_pooled = off; off += align_up(sizeof(float) * bkv * N);       // ranking keys
+    s.off_ckey = off; off += align_up(sizeof(uint32_t) * bkv * N);      // candidate list (long sequences)
+    s.off_cpos = off; off += align_up(sizeof(int32_t) * bkv * N);
+    s.off_hist = off; off += align_up(sizeof(int) * bkv * (size_t)ems::select_coarse_bins());
+    s.off_sums = off; off += align_up(sizeof(float) * bkv * chunks * 2);
+    s.off_count = off; off += align_up(sizeof(int) * bkv * chunks);
+    s.off_info = off; off += align_up(sizeof(int) * bkv * 2);
+    s.total = off;
+    return s;
 }
+
+size_t select_ws_bytes(const ems_params* p) { return plan_select(p).total; }
 
 size_t merge_ws_bytes(const ems_params* p)
 {
@@ -242,8 +257,15 @@ int ems_select(const ems_params* p, const float* s_glo, const float* s_loc,
 
     ems::SelectArgs a{};
     a.s_glo = s_glo; a.s_loc = s_loc; a.s_gl_opt = s_gl_opt;
-    a.pooled = static_cast<float*>(ws);
-    a.comb = reinterpret_cast<float*>(static_cast<char*>(ws) + select_ws_bytes(p) / 2);
+    const SelectPlan sp = plan_select(p);
+    char* w = static_cast<char*>(ws);
+    a.pooled = reinterpret_cast<float*>(w + sp.off_pooled);
+    a.cand_key = reinterpret_cast<uint32_t*>(w + sp.off_ckey);
+    a.cand_pos = reinterpret_cast<int32_t*>(w + sp.off_cpos);
+    a.coarse_hist = reinterpret_cast<int*>(w + sp.off_hist);
+    a.chunk_sums = reinterpret_cast<float*>(w + sp.off_sums);
+    a.chunk_count = reinterpret_cast<int*>(w + sp.off_count);
+    a.head_info = reinterpret_cast<int*>(w + sp.off_info);
     a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
     a.bkv = p->batch * p->kv_heads; a.seq_len = p->seq_len; a.window = p->window;
     a.n_imp = n_imp; a.n_tbm = n_tbm; a.pool_kernel = p->pool_kernel;

@@ -32,8 +32,14 @@ struct SelectArgs {
     const float* s_glo;
     const float* s_loc;
     float* s_gl_opt;    // nullable
-    float* pooled;      // [B*Hkv, N] workspace (ranking keys)
-    float* comb;        // [B*Hkv, N] workspace (Eq. 2 vector before pooling; long sequences only)
+    float* pooled;      // [B*Hkv, N] workspace (pooled score = ranking keys; short sequences: Eq. 2 vector)
+    // long sequences only (workspace):
+    uint32_t* cand_key; // [B*Hkv, N] candidates' keys in integer order form, position order
+    int32_t* cand_pos;  // [B*Hkv, N] their positions
+    int* coarse_hist;   // [B*Hkv, select_coarse_bins()] keys per leading-bit bin
+    float* chunk_sums;  // [B*Hkv, chunks, 2] sums of s_glo / s_loc per chunk
+    int* chunk_count;   // [B*Hkv, chunks] candidates per chunk
+    int* head_info;     // [B*Hkv, 2] lowest candidate bin, length of the candidate list
     int32_t* imp_idx;
     int32_t* tbm_idx;
     int bkv, seq_len, window, n_imp, n_tbm, pool_kernel;
@@ -127,6 +133,8 @@ struct StatsArgs {
 };
 
 int score_keys_per_block(int dtype_is_f32);
+int select_chunks(int seq_len);     // blocks per head of the long-sequence select
+int select_coarse_bins();
 hipError_t launch_sparsity(const StatsArgs& a, hipStream_t st);
 hipError_t launch_redundancy(const StatsArgs& a, bool f32, hipStream_t st);
 hipError_t launch_decode_init(const DecodeInitArgs& a, bool f32, hipStream_t st);

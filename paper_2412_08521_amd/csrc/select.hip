@@ -1,6 +1,7 @@
 // Global-Local score (Eq. 2), mean pooling and token partition (Sec. 4.2).
 //
-// One block per (batch, kv-head).  The block
+// Short sequences: one block per (batch, kv-head), keys in registers (select_reg_kernel).
+// Long sequences: the O(N) part is spread over many blocks per head (see below).  Either way:
 //   1. sums s_glo and s_loc (fixed-order tree) to get the mean-alignment factor of Eq. 2,
 //   2. forms s = max(s_glo * factor, s_loc) and its zero-padded mean pool, written as the
 //      ranking key of every position,
@@ -48,9 +49,197 @@ __device__ __forceinline__ void hist_add(int* hist, int digit, bool on)
     if (on && digit != d0) atomicAdd(&hist[digit], 1);
 }
 
-__global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
+// ------------------------------------------------------------------------------------
+// Long sequences: every head is cut into chunks of kChunk positions, one block each, so that
+// the whole chip works on the O(N) part; the exact ranking is then done by one block per head
+// on a short list of candidates.  Five launches, in stream order:
+//   A  select_sums_kernel     per-chunk sums of s_glo and s_loc (fixed-order trees)
+//   B  select_keys_kernel     Eq. 2 with the head's factor (chunk sums added in chunk order),
+//                             mean pooling, ranking keys written, and a histogram of the keys'
+//                             12 leading bits per head (integer atomics: order-free)
+//   C  select_count_kernel    the leading-bit bin that holds the last rank wanted (N_imp +
+//                             N_tbm): every key in that bin or above is a candidate; how many
+//                             candidates each chunk holds
+//   D  select_gather_kernel   candidates (key, position) written in position order
+//   E  select_finish_kernel   exact radix select of the two cut ranks over the candidates and
+//                             ordered write of the two index sets
+// The candidate list always contains every token of rank <= N_imp + N_tbm; with ties in the
+// leading bits it is longer (in the extreme, all positions), which only costs time.
+// ------------------------------------------------------------------------------------
+constexpr int kChunk = 2048;          // positions per block in launches A-D
+constexpr int kChunkBlock = 256;
+constexpr int kPerThread = kChunk / kChunkBlock;
+constexpr int kCoarseBits = 12, kCoarseBins = 1 << kCoarseBits;
+
+__global__ __launch_bounds__(kChunkBlock) void select_sums_kernel(SelectArgs a)
 {
-    __shared__ float red[kSelWaves][2];
+    __shared__ float red[kChunkBlock / kWave][2];
+    const int N = a.seq_len, head = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+    const float* glo = a.s_glo + (size_t)head * N;
+    const float* loc = a.s_loc + (size_t)head * N;
+    const int c0 = blk * kChunk;
+    float sg = 0.f, sl = 0.f;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int j = c0 + i * kChunkBlock + tid;
+        if (j < N) { sg += glo[j]; sl += loc[j]; }
+    }
+    sg = wave_sum(sg); sl = wave_sum(sl);
+    if (tid % kWave == 0) { red[tid / kWave][0] = sg; red[tid / kWave][1] = sl; }
+    __syncthreads();
+    if (tid == 0) {
+        float tg = 0.f, tl = 0.f;
+        for (int w = 0; w < kChunkBlock / kWave; ++w) { tg += red[w][0]; tl += red[w][1]; }
+        a.chunk_sums[((size_t)head * gridDim.x + blk) * 2 + 0] = tg;
+        a.chunk_sums[((size_t)head * gridDim.x + blk) * 2 + 1] = tl;
+    }
+    // the head's histogram starts from zero (launch B adds to it)
+    if (blk == 0)
+        for (int b = tid; b < kCoarseBins; b += kChunkBlock) a.coarse_hist[(size_t)head * kCoarseBins + b] = 0;
+}
+
+__global__ __launch_bounds__(kChunkBlock) void select_keys_kernel(SelectArgs a)
+{
+    extern __shared__ float comb_sm[];                     // chunk + halo on both sides
+    __shared__ int hist[kCoarseBins];
+    __shared__ float align_sm;
+    const int N = a.seq_len, Nc = N - a.window, head = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+    const float* glo = a.s_glo + (size_t)head * N;
+    const float* loc = a.s_loc + (size_t)head * N;
+    for (int b = tid; b < kCoarseBins; b += kChunkBlock) hist[b] = 0;
+    if (tid == 0) {                                        // Eq. 2 factor: chunk sums in chunk order
+        float tg = 0.f, tl = 0.f;
+        for (int c = 0; c < (int)gridDim.x; ++c) {
+            tg += a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 0];
+            tl += a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 1];
+        }
+        align_sm = (tl / (float)N) / (tg / (float)N);
+    }
+    __syncthreads();
+    const float align = align_sm;
+    const int half = (a.pool_kernel - 1) / 2;
+    const int c0 = blk * kChunk;
+    for (int i = tid; i < kChunk + 2 * half; i += kChunkBlock) {
+        const int j = c0 - half + i;
+        comb_sm[i] = (j >= 0 && j < N) ? fmaxf(glo[j] * align, loc[j]) : 0.f;   // zero padding
+    }
+    __syncthreads();
+    const float div = (float)a.pool_kernel;
+    float* pooled = a.pooled + (size_t)head * N;
+    float* s_out = a.s_gl_opt ? a.s_gl_opt + (size_t)head * N : nullptr;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int r = i * kChunkBlock + tid, j = c0 + r;
+        float acc = 0.f;
+        for (int t = 0; t <= 2 * half; ++t) acc += comb_sm[r + t];
+        const float v = acc / div;
+        if (j < N) { pooled[j] = v; if (s_out) s_out[j] = v; }
+        hist_add(hist, (int)(order_key(v) >> (32 - kCoarseBits)), j < Nc);
+    }
+    __syncthreads();
+    int* ghist = a.coarse_hist + (size_t)head * kCoarseBins;
+    for (int b = tid; b < kCoarseBins; b += kChunkBlock)
+        if (hist[b]) atomicAdd(&ghist[b], hist[b]);
+}
+
+// The lowest leading-bit bin a candidate may have: the bin that holds rank `want` counted from
+// the top (every thread returns it).
+__device__ __forceinline__ int coarse_cut_bin(const int* ghist, int want, int* scratch /* [kChunkBlock] */)
+{
+    constexpr int kPer = kCoarseBins / kChunkBlock;        // bins per thread, taken from the top
+    const int tid = threadIdx.x;
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) mine += ghist[kCoarseBins - 1 - (tid * kPer + i)];
+    scratch[tid] = mine;
+    __syncthreads();
+    int before = 0;
+    for (int t = 0; t < tid; ++t) before += scratch[t];    // counts in the bins above this thread's
+    __syncthreads();
+    scratch[0] = 0;                                        // default: everything is a candidate
+    __syncthreads();
+    if (before < want && before + mine >= want) {
+        int cum = before;
+        for (int i = 0; i < kPer; ++i) {
+            const int bin = kCoarseBins - 1 - (tid * kPer + i);
+            cum += ghist[bin];
+            if (cum >= want) { scratch[0] = bin; break; }
+        }
+    }
+    __syncthreads();
+    const int bin = scratch[0];
+    __syncthreads();
+    return bin;
+}
+
+// thread t of a chunk block owns the kPerThread consecutive positions c0 + t * kPerThread ..
+__device__ __forceinline__ int chunk_candidates(const float* pooled, int c0, int Nc, int cut_bin, uint32_t (&key)[kPerThread])
+{
+    const int j0 = c0 + (int)threadIdx.x * kPerThread;
+    int n = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int j = j0 + i;
+        key[i] = j < Nc ? order_key(pooled[j]) : 0u;
+        n += (j < Nc && (int)(key[i] >> (32 - kCoarseBits)) >= cut_bin) ? 1 : 0;
+    }
+    return n;
+}
+
+__global__ __launch_bounds__(kChunkBlock) void select_count_kernel(SelectArgs a)
+{
+    __shared__ int scratch[kChunkBlock];
+    const int N = a.seq_len, Nc = N - a.window, head = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+    const int cut_bin = coarse_cut_bin(a.coarse_hist + (size_t)head * kCoarseBins, a.n_imp + a.n_tbm, scratch);
+    uint32_t key[kPerThread];
+    const int n = chunk_candidates(a.pooled + (size_t)head * N, blk * kChunk, Nc, cut_bin, key);
+    scratch[tid] = n;
+    __syncthreads();
+    if (tid == 0) {
+        int tot = 0;
+        for (int t = 0; t < kChunkBlock; ++t) tot += scratch[t];
+        a.chunk_count[(size_t)head * gridDim.x + blk] = tot;
+        if (blk == 0) a.head_info[head * 2] = cut_bin;
+    }
+}
+
+__global__ __launch_bounds__(kChunkBlock) void select_gather_kernel(SelectArgs a)
+{
+    __shared__ int scratch[kChunkBlock];
+    __shared__ int base_sm;
+    const int N = a.seq_len, Nc = N - a.window, head = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+    const int cut_bin = a.head_info[head * 2];
+    if (tid == 0) {
+        int before = 0, total = 0;
+        for (int c = 0; c < (int)gridDim.x; ++c) {
+            const int x = a.chunk_count[(size_t)head * gridDim.x + c];
+            if (c < blk) before += x;
+            total += x;
+        }
+        base_sm = before;
+        if (blk == 0) a.head_info[head * 2 + 1] = total;    // length of the candidate list
+    }
+    uint32_t key[kPerThread];
+    const int c0 = blk * kChunk;
+    const int n = chunk_candidates(a.pooled + (size_t)head * N, c0, Nc, cut_bin, key);
+    scratch[tid] = n;
+    __syncthreads();
+    int at = base_sm;
+    for (int t = 0; t < tid; ++t) at += scratch[t];
+    uint32_t* ckey = a.cand_key + (size_t)head * N;
+    int32_t* cpos = a.cand_pos + (size_t)head * N;
+    const int j0 = c0 + tid * kPerThread;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int j = j0 + i;
+        if (j < Nc && (int)(key[i] >> (32 - kCoarseBits)) >= cut_bin) { ckey[at] = key[i]; cpos[at] = j; ++at; }
+    }
+}
+
+// Exact two-cut selection over a head's candidate list (keys already in integer order form,
+// positions ascending): steps 3 and 4 of the header comment.
+__global__ __launch_bounds__(kSelBlock) void select_finish_kernel(SelectArgs a)
+{
     __shared__ int hist[2][256];
     __shared__ int suffix[2][257];
     __shared__ int scan_sm[kSelWaves][2];
@@ -58,41 +247,11 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
     __shared__ uint32_t sel_prefix[2];
     __shared__ int sel_rem[2];
 
-    const int N = a.seq_len, Nc = N - a.window;
+    const int N = a.seq_len;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    const float* glo = a.s_glo + (size_t)blockIdx.x * N;
-    const float* loc = a.s_loc + (size_t)blockIdx.x * N;
-    float* pooled = a.pooled + (size_t)blockIdx.x * N;
-    float* s_out = a.s_gl_opt ? a.s_gl_opt + (size_t)blockIdx.x * N : nullptr;
-
-    // ---- 1. Eq. 2 alignment factor (sum(s_loc)/N) / (sum(s_glo)/N)
-    float sg = 0.f, sl = 0.f;
-    for (int j = tid; j < N; j += kSelBlock) { sg += glo[j]; sl += loc[j]; }
-    sg = wave_sum(sg); sl = wave_sum(sl);
-    if (lane == 0) { red[wave][0] = sg; red[wave][1] = sl; }
-    __syncthreads();
-    float tot_g = 0.f, tot_l = 0.f;
-    for (int w = 0; w < kSelWaves; ++w) { tot_g += red[w][0]; tot_l += red[w][1]; }
-    const float align = (tot_l / (float)N) / (tot_g / (float)N);
-
-    // ---- 2. element-wise max, staged through the workspace, then mean pooling (zero padding,
-    // divisor = kernel width)
-    float* comb = a.comb + (size_t)blockIdx.x * N;
-    for (int j = tid; j < N; j += kSelBlock) comb[j] = fmaxf(glo[j] * align, loc[j]);
-    __syncthreads();   // this block's global writes are visible to the whole block
-    const int half = (a.pool_kernel - 1) / 2;
-    const float inv_div = (float)a.pool_kernel;
-    for (int j = tid; j < N; j += kSelBlock) {
-        float acc = 0.f;
-        for (int t = -half; t <= half; ++t) {
-            const int jj = j + t;
-            if (jj >= 0 && jj < N) acc += comb[jj];
-        }
-        const float v = acc / inv_div;
-        pooled[j] = v;
-        if (s_out) s_out[j] = v;
-    }
-    __syncthreads();   // this block's global writes are visible to the whole block
+    const int M = a.head_info[blockIdx.x * 2 + 1];
+    const uint32_t* ckey = a.cand_key + (size_t)blockIdx.x * N;
+    const int32_t* cpos = a.cand_pos + (size_t)blockIdx.x * N;
 
     // ---- 3. radix select of two ranks (1-based, counted from the largest key)
     if (tid < 2) {
@@ -104,17 +263,17 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
         __syncthreads();
         const uint32_t p0 = sel_prefix[0], p1 = sel_prefix[1];
         const bool same_prefix = shift == 24 || p0 == p1;
-        // eight keys in flight per thread: the loop is bound by load latency otherwise
-        for (int j0 = tid; j0 < Nc; j0 += kSelBlock * kSelUnroll) {
+        for (int j0 = tid; j0 < M; j0 += kSelBlock * kSelUnroll) {
             uint32_t key[kSelUnroll];
 #pragma unroll
             for (int u = 0; u < kSelUnroll; ++u) {
                 const int j = j0 + u * kSelBlock;
-                key[u] = j < Nc ? order_key(pooled[j]) : 0u;
+                key[u] = j < M ? ckey[j] : 0u;
             }
 #pragma unroll
             for (int u = 0; u < kSelUnroll; ++u) {
-                const bool ok = j0 + u * kSelBlock < Nc;
+                const bool ok = j0 + u * kSelBlock < M;
+                if (__ballot(ok) == 0ull) continue;                  // wave-uniform
                 const uint32_t hi = shift == 24 ? 0u : (key[u] >> (shift + 8));
                 const int digit = (key[u] >> shift) & 255;
                 hist_add(hist[0], digit, ok && (shift == 24 || hi == p0));
@@ -124,8 +283,7 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
         __syncthreads();
         if (same_prefix && tid < 256) hist[1][tid] = hist[0][tid];   // one count serves both cuts
         __syncthreads();
-        // suffix[t][d] = number of matching keys with digit >= d: an inclusive scan over
-        // the digits taken from 255 downwards, 256 threads per target (4 waves each).
+        // suffix[t][d] = number of matching keys with digit >= d
         int incl = 0;
         if (tid < 512) {
             incl = hist[tid >> 8][255 - (tid & 255)];
@@ -164,39 +322,29 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
     const int G1 = k1 - need1;                    // keys greater than T1
     const int G2 = k2 - sel_rem[1];               // keys greater than T2
 
-    // ---- 4. ordered classification: rank = #greater + #equal at lower positions.
-    // Every wave owns a contiguous range of positions and walks it 64 at a time (coalesced);
-    // ordinals inside a step come from ballots, across steps from running counters, across
-    // waves from a scan over the 16 wave totals.
-    const int per_wave = ((Nc + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-    const int w0 = min(wave * per_wave, Nc), w1 = min(w0 + per_wave, Nc);
+    // ---- 4. ordered classification: rank = #greater + #equal at lower positions.  Every wave
+    // owns a contiguous range of the list and walks it 64 at a time; ordinals inside a step come
+    // from ballots, across steps from running counters, across waves from a scan over the wave totals.
+    const int per_wave = ((M + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+    const int w0 = min(wave * per_wave, M), w1 = min(w0 + per_wave, M);
     const unsigned long long below = (1ull << lane) - 1ull;
-    auto wave_prefix = [&](int mine, int& before, int& total) {     // exclusive scan over waves
+    auto wave_prefix = [&](int mine, int& before) {                 // exclusive scan over waves
         __syncthreads();
         if (lane == 0) scan_sm[wave][0] = mine;
         __syncthreads();
-        before = 0; total = 0;
-        for (int w = 0; w < kSelWaves; ++w) { const int x = scan_sm[w][0]; if (w < wave) before += x; total += x; }
+        before = 0;
+        for (int w = 0; w < wave; ++w) before += scan_sm[w][0];
     };
-    // pass A: how many keys equal to each cut value does every wave hold
     int eq1 = 0, eq2 = 0;
-    for (int j0 = w0 + lane; j0 < w1 + lane; j0 += kWave * kSelUnroll) {
-        uint32_t key[kSelUnroll];
-#pragma unroll
-        for (int u = 0; u < kSelUnroll; ++u) {
-            const int j = j0 + u * kWave;
-            key[u] = j < w1 ? order_key(pooled[j]) : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < kSelUnroll; ++u) {
-            const bool ok = j0 + u * kWave < w1;
-            eq1 += __popcll(__ballot(ok && key[u] == T1));
-            eq2 += __popcll(__ballot(ok && key[u] == T2));
-        }
+    for (int j = w0 + lane; j < w1 + lane; j += kWave) {
+        const bool ok = j < w1;
+        const uint32_t key = ok ? ckey[j] : 0u;
+        eq1 += __popcll(__ballot(ok && key == T1));
+        eq2 += __popcll(__ballot(ok && key == T2));
     }
-    int o1, o2, tot;
-    wave_prefix(eq1, o1, tot);
-    wave_prefix(eq2, o2, tot);
+    int o1, o2;
+    wave_prefix(eq1, o1);
+    wave_prefix(eq2, o2);
     auto classify = [&](uint32_t key, bool ok, int& r1, int& r2, bool& is_imp, bool& is_tbm) {
         const unsigned long long m1 = __ballot(ok && key == T1), m2 = __ballot(ok && key == T2);
         int rank;
@@ -207,55 +355,34 @@ __global__ __launch_bounds__(kSelBlock) void select_kernel(SelectArgs a)
         is_imp = ok && rank < k1;
         is_tbm = ok && rank >= k1 && rank < k2;
     };
-    // pass B: how many important / to-be-merged tokens does every wave hold
     int c_imp = 0, c_tbm = 0;
     {
         int r1 = o1, r2 = o2;
-        for (int j0 = w0 + lane; j0 < w1 + lane; j0 += kWave * kSelUnroll) {
-            uint32_t key[kSelUnroll];
-#pragma unroll
-            for (int u = 0; u < kSelUnroll; ++u) {
-                const int j = j0 + u * kWave;
-                key[u] = j < w1 ? order_key(pooled[j]) : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < kSelUnroll; ++u) {
-                const bool ok = j0 + u * kWave < w1;
-                if (__ballot(ok && key[u] >= T2) == 0ull) continue;   // wave-uniform: nothing to rank here
-                bool ii, tt;
-                classify(key[u], ok, r1, r2, ii, tt);
-                c_imp += __popcll(__ballot(ii));
-                c_tbm += __popcll(__ballot(tt));
-            }
+        for (int j = w0 + lane; j < w1 + lane; j += kWave) {
+            const bool ok = j < w1;
+            const uint32_t key = ok ? ckey[j] : 0u;
+            bool ii, tt;
+            classify(key, ok, r1, r2, ii, tt);
+            c_imp += __popcll(__ballot(ii));
+            c_tbm += __popcll(__ballot(tt));
         }
     }
     int bi, bt;
-    wave_prefix(c_imp, bi, tot);
-    wave_prefix(c_tbm, bt, tot);
-    // pass C: write the positions, ascending
+    wave_prefix(c_imp, bi);
+    wave_prefix(c_tbm, bt);
     int32_t* imp = a.imp_idx + (size_t)blockIdx.x * a.n_imp;
     int32_t* tbm = a.tbm_idx ? a.tbm_idx + (size_t)blockIdx.x * a.n_tbm : nullptr;
     {
         int r1 = o1, r2 = o2;
-        for (int j0 = w0 + lane; j0 < w1 + lane; j0 += kWave * kSelUnroll) {
-            uint32_t key[kSelUnroll];
-#pragma unroll
-            for (int u = 0; u < kSelUnroll; ++u) {
-                const int j = j0 + u * kWave;
-                key[u] = j < w1 ? order_key(pooled[j]) : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < kSelUnroll; ++u) {
-                const int j = j0 + u * kWave;
-                const bool ok = j < w1;
-                if (__ballot(ok && key[u] >= T2) == 0ull) continue;   // wave-uniform
-                bool ii, tt;
-                classify(key[u], ok, r1, r2, ii, tt);
-                const unsigned long long mi = __ballot(ii), mt = __ballot(tt);
-                if (ii) { const int at = bi + __popcll(mi & below); if (at < a.n_imp) imp[at] = j; }
-                if (tt && tbm) { const int at = bt + __popcll(mt & below); if (at < a.n_tbm) tbm[at] = j; }
-                bi += __popcll(mi); bt += __popcll(mt);
-            }
+        for (int j = w0 + lane; j < w1 + lane; j += kWave) {
+            const bool ok = j < w1;
+            const uint32_t key = ok ? ckey[j] : 0u;
+            bool ii, tt;
+            classify(key, ok, r1, r2, ii, tt);
+            const unsigned long long mi = __ballot(ii), mt = __ballot(tt);
+            if (ii) { const int at = bi + __popcll(mi & below); if (at < a.n_imp) imp[at] = cpos[j]; }
+            if (tt && tbm) { const int at = bt + __popcll(mt & below); if (at < a.n_tbm) tbm[at] = cpos[j]; }
+            bi += __popcll(mi); bt += __popcll(mt);
         }
     }
 }
@@ -462,9 +589,17 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t st)
 {
     if (a.seq_len <= kSelBlock * 2) return launch_select_reg<2>(a, st);
     if (a.seq_len <= kSelBlock * 8) return launch_select_reg<8>(a, st);
-    if (a.seq_len <= kSelBlock * 32) return launch_select_reg<32>(a, st);
-    hipLaunchKernelGGL(select_kernel, dim3((unsigned)a.bkv), dim3(kSelBlock), 0, st, a);
+    const dim3 grid((unsigned)select_chunks(a.seq_len), (unsigned)a.bkv);
+    const size_t lds = sizeof(float) * (size_t)(kChunk + a.pool_kernel - 1);
+    hipLaunchKernelGGL(select_sums_kernel, grid, dim3(kChunkBlock), 0, st, a);
+    hipLaunchKernelGGL(select_keys_kernel, grid, dim3(kChunkBlock), lds, st, a);
+    hipLaunchKernelGGL(select_count_kernel, grid, dim3(kChunkBlock), 0, st, a);
+    hipLaunchKernelGGL(select_gather_kernel, grid, dim3(kChunkBlock), 0, st, a);
+    hipLaunchKernelGGL(select_finish_kernel, dim3((unsigned)a.bkv), dim3(kSelBlock), 0, st, a);
     return hipGetLastError();
 }
+
+int select_chunks(int seq_len) { return (seq_len + kChunk - 1) / kChunk; }
+int select_coarse_bins() { return kCoarseBins; }
 
 }  // namespace ems

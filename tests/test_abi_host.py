@@ -179,14 +179,19 @@ int main(void) {
     assert all(int(x) % 256 == 0 for x in out[3:7]) and "workspace" in " ".join(out[7:])
 
 
-def test_probe_argument_errors(lib):
+def test_probe_library_is_separate_and_checks_arguments(lib):
+    """The benchmark's measurement kernels live in a library of their own."""
+    from paper_2412_08521_amd import bench_probe
+    assert not hasattr(lib, "ems_probe_mfma") and not hasattr(lib, "ems_probe_copy")
+    pl = bench_probe.lib()
     d = C.c_void_p(256)
-    assert lib.ems_probe_mfma(0, 10, d, None) == B.EMS_ERR_INVALID_ARG
-    assert lib.ems_probe_mfma(8, 0, d, None) == B.EMS_ERR_INVALID_ARG
-    assert lib.ems_probe_mfma(8, 10, None, None) == B.EMS_ERR_INVALID_ARG
-    assert lib.ems_probe_copy(d, d, 24, None) == B.EMS_ERR_INVALID_ARG      # not a multiple of 16
-    assert lib.ems_probe_copy(C.c_void_p(8), d, 32, None) == B.EMS_ERR_INVALID_ARG
-    assert lib.ems_probe_copy(None, d, 32, None) == B.EMS_ERR_INVALID_ARG
+    assert pl.ems_probe_mfma(0, 10, None, d, None) == -1
+    assert pl.ems_probe_mfma(8, 0, None, d, None) == -1
+    assert pl.ems_probe_mfma(8, 10, None, None, None) == -1
+    assert pl.ems_probe_mfma(8, 10, C.c_void_p(8), d, None) == -1          # misaligned operand buffer
+    assert pl.ems_probe_copy(d, d, 24, None) == -1                           # not a multiple of 16
+    assert pl.ems_probe_copy(C.c_void_p(8), d, 32, None) == -1
+    assert pl.ems_probe_copy(None, d, 32, None) == -1
 
 
 def test_binding_rejects_host_tensors_and_wrong_shapes(lib):

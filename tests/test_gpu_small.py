@@ -502,11 +502,16 @@ def test_zero_keys_identical_keys_and_full_budget(mode):
 
 
 def test_probe_kernels_run():
-    """The measurement kernels: the copy copies, the MFMA loop leaves finite values."""
+    """The benchmark's measurement kernels: the copy copies, the MFMA loop leaves finite values."""
+    from paper_2412_08521_amd import bench_probe
     src = torch.randn(1 << 20, device="cuda")
     dst = torch.zeros_like(src)
-    assert B.ems_probe_copy(src, dst) == 2 * src.numel() * 4
+    assert bench_probe.probe_copy(src, dst) == 2 * src.numel() * 4
     sink = torch.empty(8 * 256, dtype=torch.float32, device="cuda")
-    assert B.ems_probe_mfma(8, 10, sink) == 8 * 4 * 10 * 4 * 32768
+    assert bench_probe.probe_mfma(8, 10, sink) == 8 * 4 * 10 * 32 * 32768
     torch.cuda.synchronize()
     assert torch.equal(src, dst) and torch.isfinite(sink).all()
+    ops = torch.randn(bench_probe.OPERAND_BYTES // 2, device="cuda").to(torch.bfloat16)
+    bench_probe.probe_mfma(8, 100, sink, operands=ops)
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all()
