@@ -114,7 +114,7 @@ SelectPlan plan_select(const ems_params* p)
     s.off_cpos = off; off += align_up(sizeof(int32_t) * bkv * N);
     s.off_hist = off; off += align_up(sizeof(int) * bkv * (size_t)ems::select_coarse_bins());
     s.off_sums = off; off += align_up(sizeof(float) * bkv * chunks * 2);
-    s.off_count = off; off += align_up(sizeof(int) * bkv * chunks);
+    s.off_count = off; off += align_up(sizeof(int) * bkv * chunks * 2);
     s.off_info = off; off += align_up(sizeof(int) * bkv * 2);
     s.total = off;
     return s;
@@ -266,6 +266,7 @@ int ems_select(const ems_params* p, const float* s_glo, const float* s_loc,
     a.chunk_sums = reinterpret_cast<float*>(w + sp.off_sums);
     a.chunk_count = reinterpret_cast<int*>(w + sp.off_count);
     a.head_info = reinterpret_cast<int*>(w + sp.off_info);
+    a.n_chunks = ems::select_chunks(p->seq_len);
     a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
     a.bkv = p->batch * p->kv_heads; a.seq_len = p->seq_len; a.window = p->window;
     a.n_imp = n_imp; a.n_tbm = n_tbm; a.pool_kernel = p->pool_kernel;

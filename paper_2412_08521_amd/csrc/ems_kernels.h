@@ -38,8 +38,9 @@ struct SelectArgs {
     int32_t* cand_pos;  // [B*Hkv, N] their positions
     int* coarse_hist;   // [B*Hkv, select_coarse_bins()] keys per leading-bit bin
     float* chunk_sums;  // [B*Hkv, chunks, 2] sums of s_glo / s_loc per chunk
-    int* chunk_count;   // [B*Hkv, chunks] candidates per chunk
-    int* head_info;     // [B*Hkv, 2] lowest candidate bin, length of the candidate list
+    int* chunk_count;   // [B*Hkv, chunks, 2] where a chunk's candidates start in the list, how many
+    int* head_info;     // [B*Hkv] list cursor (ends as the length of the candidate list)
+    int n_chunks;       // select_chunks(seq_len)
     int32_t* imp_idx;
     int32_t* tbm_idx;
     int bkv, seq_len, window, n_imp, n_tbm, pool_kernel;

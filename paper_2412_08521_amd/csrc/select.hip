@@ -35,6 +35,29 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// Exclusive prefix sum of one int per thread over a block of kThreads (a multiple of 64, at most
+// 1024); `total` gets the block's sum.  `sm` holds kThreads / 64 + 1 ints.  Every thread calls it.
+template <int kThreads>
+__device__ __forceinline__ int block_excl_scan(int v, int* sm, int& total)
+{
+    constexpr int kW = kThreads / kWave;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int u = __shfl_up(incl, o);
+        if (lane >= o) incl += u;
+    }
+    __syncthreads();                                      // sm may still be read from an earlier call
+    if (lane == kWave - 1) sm[wave] = incl;
+    __syncthreads();
+    int before = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) { const int x = sm[w]; before += w < wave ? x : 0; tot += x; }
+    total = tot;
+    return before + incl - v;
+}
+
 // One histogram update per lane (if `on`).  Scores share their leading digits, so most
 // lanes of a wave hit the same bin: the lanes that agree with the first active lane are
 // counted with one ballot and one atomic, the others fall back to their own atomic.
@@ -52,16 +75,15 @@ __device__ __forceinline__ void hist_add(int* hist, int digit, bool on)
 // ------------------------------------------------------------------------------------
 // Long sequences: every head is cut into chunks of kChunk positions, one block each, so that
 // the whole chip works on the O(N) part; the exact ranking is then done by one block per head
-// on a short list of candidates.  Five launches, in stream order:
+// on a short list of candidates.  Four launches, in stream order:
 //   A  select_sums_kernel     per-chunk sums of s_glo and s_loc (fixed-order trees)
 //   B  select_keys_kernel     Eq. 2 with the head's factor (chunk sums added in chunk order),
 //                             mean pooling, ranking keys written, and a histogram of the keys'
 //                             12 leading bits per head (integer atomics: order-free)
-//   C  select_count_kernel    the leading-bit bin that holds the last rank wanted (N_imp +
-//                             N_tbm): every key in that bin or above is a candidate; how many
-//                             candidates each chunk holds
-//   D  select_gather_kernel   candidates (key, position) written in position order
-//   E  select_finish_kernel   exact radix select of the two cut ranks over the candidates and
+//   C  select_gather_kernel   the leading-bit bin that holds the last rank wanted (N_imp +
+//                             N_tbm): every key in that bin or above is a candidate; each chunk
+//                             appends its candidates (key, position), in position order
+//   D  select_finish_kernel   exact radix select of the two cut ranks over the candidates and
 //                             ordered write of the two index sets
 // The candidate list always contains every token of rank <= N_imp + N_tbm; with ties in the
 // leading bits it is longer (in the extreme, all positions), which only costs time.
@@ -93,9 +115,11 @@ __global__ __launch_bounds__(kChunkBlock) void select_sums_kernel(SelectArgs a)
         a.chunk_sums[((size_t)head * gridDim.x + blk) * 2 + 0] = tg;
         a.chunk_sums[((size_t)head * gridDim.x + blk) * 2 + 1] = tl;
     }
-    // the head's histogram starts from zero (launch B adds to it)
-    if (blk == 0)
+    // the head's histogram and list cursor start from zero (launches B and C add to them)
+    if (blk == 0) {
         for (int b = tid; b < kCoarseBins; b += kChunkBlock) a.coarse_hist[(size_t)head * kCoarseBins + b] = 0;
+        if (tid == 0) a.head_info[head] = 0;
+    }
 }
 
 __global__ __launch_bounds__(kChunkBlock) void select_keys_kernel(SelectArgs a)
@@ -107,21 +131,43 @@ __global__ __launch_bounds__(kChunkBlock) void select_keys_kernel(SelectArgs a)
     const float* glo = a.s_glo + (size_t)head * N;
     const float* loc = a.s_loc + (size_t)head * N;
     for (int b = tid; b < kCoarseBins; b += kChunkBlock) hist[b] = 0;
-    if (tid == 0) {                                        // Eq. 2 factor: chunk sums in chunk order
-        float tg = 0.f, tl = 0.f;
-        for (int c = 0; c < (int)gridDim.x; ++c) {
-            tg += a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 0];
-            tl += a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 1];
-        }
-        align_sm = (tl / (float)N) / (tg / (float)N);
+    // all of the chunk's loads are in flight while the factor is being formed
+    const int c0 = blk * kChunk;
+    float g[kPerThread], l[kPerThread];
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int j = c0 + i * kChunkBlock + tid;
+        g[i] = j < N ? glo[j] : 0.f;
+        l[i] = j < N ? loc[j] : 0.f;
     }
+    // Eq. 2 factor: the chunk sums are fetched by as many threads at once and added in chunk order
+    __shared__ float sums_sm[2 * kChunkBlock];
+    float tg = 0.f, tl = 0.f;
+    for (int c0s = 0; c0s < (int)gridDim.x; c0s += kChunkBlock) {
+        const int c = c0s + tid;
+        if (c < (int)gridDim.x) {
+            sums_sm[2 * tid] = a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 0];
+            sums_sm[2 * tid + 1] = a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 1];
+        }
+        __syncthreads();
+        if (tid == 0)
+            for (int c = 0; c < min(kChunkBlock, (int)gridDim.x - c0s); ++c) { tg += sums_sm[2 * c]; tl += sums_sm[2 * c + 1]; }
+        __syncthreads();
+    }
+    if (tid == 0) align_sm = (tl / (float)N) / (tg / (float)N);
     __syncthreads();
     const float align = align_sm;
     const int half = (a.pool_kernel - 1) / 2;
-    const int c0 = blk * kChunk;
-    for (int i = tid; i < kChunk + 2 * half; i += kChunkBlock) {
-        const int j = c0 - half + i;
-        comb_sm[i] = (j >= 0 && j < N) ? fmaxf(glo[j] * align, loc[j]) : 0.f;   // zero padding
+    {
+        for (int i = tid; i < 2 * half; i += kChunkBlock) {      // the halo: `half` positions on either side
+            const int j = i < half ? c0 - half + i : c0 + kChunk + (i - half);
+            comb_sm[i < half ? i : kChunk + i] = (j >= 0 && j < N) ? fmaxf(glo[j] * align, loc[j]) : 0.f;   // zero padding
+        }
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            const int j = c0 + i * kChunkBlock + tid;
+            comb_sm[half + i * kChunkBlock + tid] = j < N ? fmaxf(g[i] * align, l[i]) : 0.f;
+        }
     }
     __syncthreads();
     const float div = (float)a.pool_kernel;
@@ -144,88 +190,66 @@ __global__ __launch_bounds__(kChunkBlock) void select_keys_kernel(SelectArgs a)
 
 // The lowest leading-bit bin a candidate may have: the bin that holds rank `want` counted from
 // the top (every thread returns it).
-__device__ __forceinline__ int coarse_cut_bin(const int* ghist, int want, int* scratch /* [kChunkBlock] */)
+__device__ __forceinline__ int coarse_cut_bin(const int* ghist, int want, int* scratch /* [kChunkBlock / 64 + 2] */)
 {
     constexpr int kPer = kCoarseBins / kChunkBlock;        // bins per thread, taken from the top
     const int tid = threadIdx.x;
-    int mine = 0;
+    int cnt[kPer], mine = 0;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) mine += ghist[kCoarseBins - 1 - (tid * kPer + i)];
-    scratch[tid] = mine;
+    for (int i = 0; i < kPer; ++i) { cnt[i] = ghist[kCoarseBins - 1 - (tid * kPer + i)]; mine += cnt[i]; }
+    int total;
+    const int before = block_excl_scan<kChunkBlock>(mine, scratch, total);   // counts in the bins above this thread's
+    int* answer = scratch + kChunkBlock / kWave + 1;
+    if (tid == 0) *answer = 0;                             // fewer keys than wanted: everything is a candidate
     __syncthreads();
-    int before = 0;
-    for (int t = 0; t < tid; ++t) before += scratch[t];    // counts in the bins above this thread's
-    __syncthreads();
-    scratch[0] = 0;                                        // default: everything is a candidate
-    __syncthreads();
-    if (before < want && before + mine >= want) {
+    if (before < want && before + mine >= want) {          // exactly one thread
         int cum = before;
+#pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int bin = kCoarseBins - 1 - (tid * kPer + i);
-            cum += ghist[bin];
-            if (cum >= want) { scratch[0] = bin; break; }
+            cum += cnt[i];
+            if (cum >= want) { *answer = kCoarseBins - 1 - (tid * kPer + i); break; }
         }
     }
     __syncthreads();
-    const int bin = scratch[0];
-    __syncthreads();
-    return bin;
+    return *answer;
 }
 
-// thread t of a chunk block owns the kPerThread consecutive positions c0 + t * kPerThread ..
-__device__ __forceinline__ int chunk_candidates(const float* pooled, int c0, int Nc, int cut_bin, uint32_t (&key)[kPerThread])
+// Launch C: the candidates of a chunk, in position order, appended to the head's list.  A chunk
+// reserves its stretch of the list with one integer atomic, so the stretches follow each other
+// in whatever order the blocks arrive; where each chunk's stretch starts and how long it is is
+// recorded, and launch D reads the list chunk by chunk -- its result does not depend on the
+// arrival order.
+__global__ __launch_bounds__(kChunkBlock) void select_gather_kernel(SelectArgs a)
 {
-    const int j0 = c0 + (int)threadIdx.x * kPerThread;
+    __shared__ int scratch[kChunkBlock / kWave + 2];
+    __shared__ int base_sm;
+    const int N = a.seq_len, Nc = N - a.window, head = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+    // the chunk's keys are requested before the histogram is scanned (independent round trips)
+    const int c0 = blk * kChunk;
+    float pv[kPerThread];
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+        const int j = c0 + tid * kPerThread + i;
+        pv[i] = j < Nc ? (a.pooled + (size_t)head * N)[j] : 0.f;
+    }
+    const int cut_bin = coarse_cut_bin(a.coarse_hist + (size_t)head * kCoarseBins, a.n_imp + a.n_tbm, scratch);
+    uint32_t key[kPerThread];
     int n = 0;
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
-        const int j = j0 + i;
-        key[i] = j < Nc ? order_key(pooled[j]) : 0u;
+        const int j = c0 + tid * kPerThread + i;
+        key[i] = j < Nc ? order_key(pv[i]) : 0u;
         n += (j < Nc && (int)(key[i] >> (32 - kCoarseBits)) >= cut_bin) ? 1 : 0;
     }
-    return n;
-}
-
-__global__ __launch_bounds__(kChunkBlock) void select_count_kernel(SelectArgs a)
-{
-    __shared__ int scratch[kChunkBlock];
-    const int N = a.seq_len, Nc = N - a.window, head = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
-    const int cut_bin = coarse_cut_bin(a.coarse_hist + (size_t)head * kCoarseBins, a.n_imp + a.n_tbm, scratch);
-    uint32_t key[kPerThread];
-    const int n = chunk_candidates(a.pooled + (size_t)head * N, blk * kChunk, Nc, cut_bin, key);
-    scratch[tid] = n;
-    __syncthreads();
+    int total;
+    const int before = block_excl_scan<kChunkBlock>(n, scratch, total);
     if (tid == 0) {
-        int tot = 0;
-        for (int t = 0; t < kChunkBlock; ++t) tot += scratch[t];
-        a.chunk_count[(size_t)head * gridDim.x + blk] = tot;
-        if (blk == 0) a.head_info[head * 2] = cut_bin;
+        base_sm = atomicAdd(&a.head_info[head], total);
+        a.chunk_count[((size_t)head * gridDim.x + blk) * 2 + 0] = base_sm;
+        a.chunk_count[((size_t)head * gridDim.x + blk) * 2 + 1] = total;
     }
-}
-
-__global__ __launch_bounds__(kChunkBlock) void select_gather_kernel(SelectArgs a)
-{
-    __shared__ int scratch[kChunkBlock];
-    __shared__ int base_sm;
-    const int N = a.seq_len, Nc = N - a.window, head = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
-    const int cut_bin = a.head_info[head * 2];
-    if (tid == 0) {
-        int before = 0, total = 0;
-        for (int c = 0; c < (int)gridDim.x; ++c) {
-            const int x = a.chunk_count[(size_t)head * gridDim.x + c];
-            if (c < blk) before += x;
-            total += x;
-        }
-        base_sm = before;
-        if (blk == 0) a.head_info[head * 2 + 1] = total;    // length of the candidate list
-    }
-    uint32_t key[kPerThread];
-    const int c0 = blk * kChunk;
-    const int n = chunk_candidates(a.pooled + (size_t)head * N, c0, Nc, cut_bin, key);
-    scratch[tid] = n;
     __syncthreads();
-    int at = base_sm;
-    for (int t = 0; t < tid; ++t) at += scratch[t];
+    int at = base_sm + before;
     uint32_t* ckey = a.cand_key + (size_t)head * N;
     int32_t* cpos = a.cand_pos + (size_t)head * N;
     const int j0 = c0 + tid * kPerThread;
@@ -236,8 +260,10 @@ __global__ __launch_bounds__(kChunkBlock) void select_gather_kernel(SelectArgs a
     }
 }
 
-// Exact two-cut selection over a head's candidate list (keys already in integer order form,
-// positions ascending): steps 3 and 4 of the header comment.
+// Launch D: exact two-cut selection over a head's candidate list (keys already in integer order
+// form): steps 3 and 4 of the header comment.  The list is a sequence of per-chunk stretches in
+// arbitrary order; position order is chunk order, then order inside the stretch.
+constexpr int kMaxChunks = (1 << 22) / kChunk;   // the interface limits seq_len to 2^22
 __global__ __launch_bounds__(kSelBlock) void select_finish_kernel(SelectArgs a)
 {
     __shared__ int hist[2][256];
@@ -246,12 +272,32 @@ __global__ __launch_bounds__(kSelBlock) void select_finish_kernel(SelectArgs a)
     __shared__ int wave_tot[8];
     __shared__ uint32_t sel_prefix[2];
     __shared__ int sel_rem[2];
+    __shared__ int ch_first[kMaxChunks + 1];     // rank (in position order) of a chunk's first candidate
+    __shared__ int ch_at[kMaxChunks];            // where its stretch starts in the list
+    __shared__ int scan17[kSelWaves + 1];
 
     const int N = a.seq_len;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    const int M = a.head_info[blockIdx.x * 2 + 1];
     const uint32_t* ckey = a.cand_key + (size_t)blockIdx.x * N;
     const int32_t* cpos = a.cand_pos + (size_t)blockIdx.x * N;
+    const int n_chunks = a.n_chunks;
+    int M = 0;
+    for (int c0 = 0; c0 < n_chunks; c0 += kSelBlock) {     // exclusive scan of the chunk lengths, in chunk order
+        const int c = c0 + tid;
+        const int len = c < n_chunks ? a.chunk_count[((size_t)blockIdx.x * n_chunks + c) * 2 + 1] : 0;
+        int total;
+        const int before = block_excl_scan<kSelBlock>(len, scan17, total);
+        if (c < n_chunks) { ch_first[c] = M + before; ch_at[c] = a.chunk_count[((size_t)blockIdx.x * n_chunks + c) * 2]; }
+        M += total;
+    }
+    if (tid == 0) ch_first[n_chunks] = M;
+    __syncthreads();
+    // list index of the candidate of rank j in position order
+    auto at_rank = [&](int j) {
+        int lo = 0, hi = n_chunks;                         // ch_first[lo] <= j < ch_first[hi]
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (ch_first[mid] <= j) lo = mid; else hi = mid; }
+        return ch_at[lo] + (j - ch_first[lo]);
+    };
 
     // ---- 3. radix select of two ranks (1-based, counted from the largest key)
     if (tid < 2) {
@@ -338,7 +384,7 @@ __global__ __launch_bounds__(kSelBlock) void select_finish_kernel(SelectArgs a)
     int eq1 = 0, eq2 = 0;
     for (int j = w0 + lane; j < w1 + lane; j += kWave) {
         const bool ok = j < w1;
-        const uint32_t key = ok ? ckey[j] : 0u;
+        const uint32_t key = ok ? ckey[at_rank(j)] : 0u;
         eq1 += __popcll(__ballot(ok && key == T1));
         eq2 += __popcll(__ballot(ok && key == T2));
     }
@@ -360,7 +406,7 @@ __global__ __launch_bounds__(kSelBlock) void select_finish_kernel(SelectArgs a)
         int r1 = o1, r2 = o2;
         for (int j = w0 + lane; j < w1 + lane; j += kWave) {
             const bool ok = j < w1;
-            const uint32_t key = ok ? ckey[j] : 0u;
+            const uint32_t key = ok ? ckey[at_rank(j)] : 0u;
             bool ii, tt;
             classify(key, ok, r1, r2, ii, tt);
             c_imp += __popcll(__ballot(ii));
@@ -376,12 +422,13 @@ __global__ __launch_bounds__(kSelBlock) void select_finish_kernel(SelectArgs a)
         int r1 = o1, r2 = o2;
         for (int j = w0 + lane; j < w1 + lane; j += kWave) {
             const bool ok = j < w1;
-            const uint32_t key = ok ? ckey[j] : 0u;
+            const int jl = ok ? at_rank(j) : 0;
+            const uint32_t key = ok ? ckey[jl] : 0u;
             bool ii, tt;
             classify(key, ok, r1, r2, ii, tt);
             const unsigned long long mi = __ballot(ii), mt = __ballot(tt);
-            if (ii) { const int at = bi + __popcll(mi & below); if (at < a.n_imp) imp[at] = cpos[j]; }
-            if (tt && tbm) { const int at = bt + __popcll(mt & below); if (at < a.n_tbm) tbm[at] = cpos[j]; }
+            if (ii) { const int at = bi + __popcll(mi & below); if (at < a.n_imp) imp[at] = cpos[jl]; }
+            if (tt && tbm) { const int at = bt + __popcll(mt & below); if (at < a.n_tbm) tbm[at] = cpos[jl]; }
             bi += __popcll(mi); bt += __popcll(mt);
         }
     }
@@ -593,7 +640,6 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t st)
     const size_t lds = sizeof(float) * (size_t)(kChunk + a.pool_kernel - 1);
     hipLaunchKernelGGL(select_sums_kernel, grid, dim3(kChunkBlock), 0, st, a);
     hipLaunchKernelGGL(select_keys_kernel, grid, dim3(kChunkBlock), lds, st, a);
-    hipLaunchKernelGGL(select_count_kernel, grid, dim3(kChunkBlock), 0, st, a);
     hipLaunchKernelGGL(select_gather_kernel, grid, dim3(kChunkBlock), 0, st, a);
     hipLaunchKernelGGL(select_finish_kernel, dim3((unsigned)a.bkv), dim3(kSelBlock), 0, st, a);
     return hipGetLastError();
