@@ -198,6 +198,28 @@ int ems_evict_merge_variant(const ems_params* p, int similarity, const void* k, 
                             void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * ems_evict_merge for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, serving loops that hold no spare buffer, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs and results as ems_evict_merge, minus `ws`:
+ * the scratch is a fixed array of EMS_STATIC_SCRATCH_BYTES in each device's global memory
+ * that belongs to the loaded library (held until the process ends).  The call allocates and
+ * frees nothing.  The HIP device of `hip_stream` must be the current device.  The first call
+ * on a device looks up that device's copy of the array (a HIP runtime query); make it once
+ * outside any graph capture.
+ *   returns EMS_ERR_WORKSPACE when the parameters need more than EMS_STATIC_SCRATCH_BYTES
+ *   (merge_ws of ems_workspace_bytes), EMS_ERR_LAUNCH when the runtime refuses the look-up
+ *   or a launch, otherwise as ems_evict_merge.
+ * All calls on one device share that device's array and it keeps the last call's contents:
+ * calls that overlap on one device (two streams, two host threads) race; serialise them.
+ */
+#define EMS_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+int ems_evict_merge_static(const ems_params* p, const void* k, const void* v,
+                           const int32_t* imp_idx, const int32_t* tbm_idx,
+                           void* k_out, void* v_out, int32_t* kept_pos,
+                           int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
+                           int32_t* slot_count, void* hip_stream);
+
+/*
  * Shared-entry expansion (App. A, "Shared Entry Expansion"; the position look-up-table of
  * Sec. 4.2).  Tokens that were merged share one cache entry; for the attention of the
  * current layer the compact cache is expanded back to one key / value per kept token.  The

@@ -29,7 +29,7 @@ EMS_STEP_FROM_STATE = -1
 
 EXPORTS = ("ems_version", "ems_strerror", "ems_partition_sizes", "ems_workspace_bytes",
            "ems_global_local_score", "ems_attention_lse", "ems_global_local_score_from_lse",
-           "ems_select", "ems_evict_merge", "ems_evict_merge_variant", "ems_expand",
+           "ems_select", "ems_evict_merge", "ems_evict_merge_variant", "ems_evict_merge_static", "ems_expand",
            "ems_decode_workspace_bytes", "ems_decode_init", "ems_decode_step",
            "ems_sparsity_rate", "ems_redundancy_rate")
 
@@ -102,6 +102,7 @@ def lib():
         l.ems_select.argtypes = [P] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         l.ems_evict_merge.argtypes = [P] + [C.c_void_p] * 12 + [C.c_size_t, C.c_void_p]
         l.ems_evict_merge_variant.argtypes = ([P, C.c_int] + [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p])
+        l.ems_evict_merge_static.argtypes = [P] + [C.c_void_p] * 12
         l.ems_expand.argtypes = [P] + [C.c_void_p] * 10
         l.ems_sparsity_rate.argtypes = [P, C.c_float] + [C.c_void_p] * 5
         l.ems_redundancy_rate.argtypes = [P] + [C.c_void_p] * 5
@@ -279,6 +280,31 @@ def ems_evict_merge(p: EmsParams, k, v, imp_idx, tbm_idx, ws=None, out=None):
                                _ptr(o["slot_count"]), _ptr(ws), ws.numel(), _stream())
     if rc != EMS_OK:
         raise EmsError(rc, "ems_evict_merge")
+    return o
+
+
+def ems_evict_merge_static(p: EmsParams, k, v, imp_idx, tbm_idx, out=None, k_norm: bool = True):
+    """ems_evict_merge on the library's fixed scratch array: no workspace, nothing allocated by the
+    call (pass `out` from alloc_evict_merge_outputs to keep the binding from allocating as well).
+    With k_norm=False no key norms are returned and they live in the scratch array."""
+    shape = (p.batch, p.kv_heads, p.seq_len, p.head_dim)
+    _check_tensor(k, shape, p.torch_dtype, "k")
+    _check_tensor(v, shape, p.torch_dtype, "v")
+    n_imp, n_tbm = ems_partition_sizes(p)
+    _check_tensor(imp_idx, (p.batch, p.kv_heads, n_imp), torch.int32, "imp_idx")
+    _check_tensor(tbm_idx, (p.batch, p.kv_heads, n_tbm), torch.int32, "tbm_idx")
+    o = dict(out) if out is not None else alloc_evict_merge_outputs(p, k.device)
+    if not k_norm:
+        o["k_norm"] = None
+    has = n_tbm > 0
+    cp = p.c()
+    rc = lib().ems_evict_merge_static(C.byref(cp), _ptr(k), _ptr(v), _ptr(imp_idx),
+                                      _ptr(tbm_idx) if has else None, _ptr(o["k_out"]), _ptr(o["v_out"]),
+                                      _ptr(o["kept_pos"]), _ptr(o["tbm_dest"]) if has else None,
+                                      _ptr(o["tbm_sim"]) if has else None, _ptr(o["k_norm"]),
+                                      _ptr(o["slot_count"]), _stream())
+    if rc != EMS_OK:
+        raise EmsError(rc, "ems_evict_merge_static")
     return o
 
 

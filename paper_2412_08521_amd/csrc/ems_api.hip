@@ -4,8 +4,36 @@
 #include "ems_kernels.h"
 
 #include <cmath>
+#include <mutex>
 
 namespace {
+
+// Scratch of ems_evict_merge_static: a fixed array in every device's global memory, part of
+// the loaded code object, so nothing is allocated for it at run time.  In host code the
+// array's name is only a handle; its address on a device comes from hipGetSymbolAddress,
+// asked once per device (static_scratch below) and kept.
+constexpr size_t kStaticScratchBytes = EMS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch`, or nullptr with *err set.
+void* static_scratch(hipError_t* err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        scratch_ptr[dev] = ptr;
+    }
+    return scratch_ptr[dev];
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -274,6 +302,48 @@ int ems_select(const ems_params* p, const float* s_glo, const float* s_loc,
     return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
 }
 
+// Argument checks shared by the evict-merge entry points.
+static bool evict_merge_args_ok(const ems_params* p, int similarity, const void* k, const void* v,
+                                const int32_t* imp_idx, const int32_t* tbm_idx,
+                                const void* k_out, const void* v_out, const int32_t* kept_pos,
+                                const int32_t* tbm_dest, const float* tbm_sim, const int32_t* slot_count,
+                                int* why)
+{
+    if (!full_params_ok(p, why)) return false;
+    *why = EMS_ERR_INVALID_ARG;
+    if (similarity != EMS_SIM_KEY && similarity != EMS_SIM_VALUE && similarity != EMS_SIM_KEY_VALUE) return false;
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+    if (!k || !v || !imp_idx || !k_out || !v_out || !kept_pos || !slot_count) return false;
+    if (n_tbm > 0 && (!tbm_idx || !tbm_dest || !tbm_sim)) return false;
+    return true;
+}
+
+// Kernel launches of the evict-merge stage on checked arguments; `ws` holds merge_ws_bytes(p).
+static int evict_merge_launch(const ems_params* p, int similarity, const void* k, const void* v,
+                              const float* token_weight_opt,
+                              const int32_t* imp_idx, const int32_t* tbm_idx,
+                              void* k_out, void* v_out, int32_t* kept_pos,
+                              int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
+                              int32_t* slot_count, void* ws, void* hip_stream)
+{
+    int n_imp, n_tbm;
+    partition_sizes(p, &n_imp, &n_tbm);
+
+    ems::MergeArgs a{};
+    a.k = k; a.v = v; a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
+    a.k_out = k_out; a.v_out = v_out; a.kept_pos = kept_pos;
+    a.tbm_dest = tbm_dest; a.tbm_sim = tbm_sim;
+    a.k_norm = k_norm_opt ? k_norm_opt : static_cast<float*>(ws);
+    a.slot_count = slot_count;
+    a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len;
+    a.window = p->window; a.budget = p->budget; a.n_imp = n_imp; a.n_tbm = n_tbm;
+    a.tau = p->tau;
+    a.weight = token_weight_opt; a.similarity = similarity;
+    const hipError_t e = ems::launch_evict_merge(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+}
+
 int ems_evict_merge(const ems_params* p, const void* k, const void* v,
                     const int32_t* imp_idx, const int32_t* tbm_idx,
                     void* k_out, void* v_out, int32_t* kept_pos,
@@ -294,27 +364,28 @@ int ems_evict_merge_variant(const ems_params* p, int similarity, const void* k, 
                             void* ws, size_t ws_bytes, void* hip_stream)
 {
     int why;
-    if (!full_params_ok(p, &why)) return why;
-    if (similarity != EMS_SIM_KEY && similarity != EMS_SIM_VALUE && similarity != EMS_SIM_KEY_VALUE)
-        return EMS_ERR_INVALID_ARG;
-    int n_imp, n_tbm;
-    partition_sizes(p, &n_imp, &n_tbm);
-    if (!k || !v || !imp_idx || !k_out || !v_out || !kept_pos || !slot_count) return EMS_ERR_INVALID_ARG;
-    if (n_tbm > 0 && (!tbm_idx || !tbm_dest || !tbm_sim)) return EMS_ERR_INVALID_ARG;
+    if (!evict_merge_args_ok(p, similarity, k, v, imp_idx, tbm_idx, k_out, v_out, kept_pos,
+                             tbm_dest, tbm_sim, slot_count, &why)) return why;
     if (!ws_ok(ws, ws_bytes, merge_ws_bytes(p))) return EMS_ERR_WORKSPACE;
+    return evict_merge_launch(p, similarity, k, v, token_weight_opt, imp_idx, tbm_idx, k_out, v_out, kept_pos,
+                              tbm_dest, tbm_sim, k_norm_opt, slot_count, ws, hip_stream);
+}
 
-    ems::MergeArgs a{};
-    a.k = k; a.v = v; a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
-    a.k_out = k_out; a.v_out = v_out; a.kept_pos = kept_pos;
-    a.tbm_dest = tbm_dest; a.tbm_sim = tbm_sim;
-    a.k_norm = k_norm_opt ? k_norm_opt : static_cast<float*>(ws);
-    a.slot_count = slot_count;
-    a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len;
-    a.window = p->window; a.budget = p->budget; a.n_imp = n_imp; a.n_tbm = n_tbm;
-    a.tau = p->tau;
-    a.weight = token_weight_opt; a.similarity = similarity;
-    const hipError_t e = ems::launch_evict_merge(a, p->dtype == EMS_F32, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
+int ems_evict_merge_static(const ems_params* p, const void* k, const void* v,
+                           const int32_t* imp_idx, const int32_t* tbm_idx,
+                           void* k_out, void* v_out, int32_t* kept_pos,
+                           int32_t* tbm_dest, float* tbm_sim, float* k_norm_opt,
+                           int32_t* slot_count, void* hip_stream)
+{
+    int why;
+    if (!evict_merge_args_ok(p, EMS_SIM_KEY, k, v, imp_idx, tbm_idx, k_out, v_out, kept_pos,
+                             tbm_dest, tbm_sim, slot_count, &why)) return why;
+    if (merge_ws_bytes(p) > kStaticScratchBytes) return EMS_ERR_WORKSPACE;
+    hipError_t err;
+    void* ws = static_scratch(&err);
+    if (!ws) return EMS_ERR_LAUNCH;
+    return evict_merge_launch(p, EMS_SIM_KEY, k, v, nullptr, imp_idx, tbm_idx, k_out, v_out, kept_pos,
+                              tbm_dest, tbm_sim, k_norm_opt, slot_count, ws, hip_stream);
 }
 
 int ems_expand(const ems_params* p, const void* k_cache, const void* v_cache,

@@ -102,6 +102,13 @@ def test_null_pointers_and_workspace_errors(lib):
     args[3] = None     # tbm_idx missing while N_tbm > 0
     assert lib.ems_evict_merge(C.byref(cp), *args, 1 << 40, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_evict_merge(C.byref(cp), *([d] * 12), 8, None) == B.EMS_ERR_WORKSPACE
+    # the allocation-free entry point: same argument checks, and a size limit instead of `ws`
+    assert lib.ems_evict_merge_static(C.byref(cp), *args, None) == B.EMS_ERR_INVALID_ARG
+    assert lib.ems_evict_merge_static(None, *([d] * 12), None) == B.EMS_ERR_INVALID_ARG
+    big = B.EmsParams(64, 32, 32, 128, 1 << 20, 32, 1 << 19, merge_ratio=0.5)
+    assert B.ems_workspace_bytes(big)[2] > 8 << 20
+    cbig = big.c()
+    assert lib.ems_evict_merge_static(C.byref(cbig), *([d] * 12), None) == B.EMS_ERR_WORKSPACE
     assert lib.ems_workspace_bytes(None, None, None, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_expand(C.byref(cp), d, d, d, d, d, None, d, d, d, None) == B.EMS_ERR_INVALID_ARG
     assert lib.ems_expand(C.byref(cp), d, d, d, None, d, d, d, d, d, None) == B.EMS_ERR_INVALID_ARG
