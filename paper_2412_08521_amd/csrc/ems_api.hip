@@ -150,12 +150,29 @@ SelectPlan plan_select(const ems_params* p)
 
 size_t select_ws_bytes(const ems_params* p) { return plan_select(p).total; }
 
-size_t merge_ws_bytes(const ems_params* p)
+// Evict-merge workspace: the key norms (used when the caller does not ask for them) and, when the
+// centre list is searched in slices, the per-slice winners.
+struct MergePlan {
+    int slice_rows, n_slices;
+    size_t off_norm, off_best, off_arg, total;
+};
+
+MergePlan plan_merge(const ems_params* p)
 {
     int n_imp, n_tbm;
     partition_sizes(p, &n_imp, &n_tbm);
-    return align_up(sizeof(float) * (size_t)p->batch * p->kv_heads * (size_t)(n_imp + n_tbm));
+    MergePlan m{};
+    ems::dest_slicing(n_imp, p->dtype == EMS_F32, &m.slice_rows, &m.n_slices);
+    const size_t bkv = (size_t)p->batch * p->kv_heads;
+    const size_t part = m.n_slices > 1 ? align_up(4 * bkv * m.n_slices * (size_t)n_tbm) : 0;
+    m.off_norm = 0;
+    m.off_best = align_up(sizeof(float) * bkv * (size_t)(n_imp + n_tbm));
+    m.off_arg = m.off_best + part;
+    m.total = m.off_arg + part;
+    return m;
 }
+
+size_t merge_ws_bytes(const ems_params* p) { return plan_merge(p).total; }
 
 bool ws_ok(const void* ws, size_t have, size_t need)
 {
@@ -334,7 +351,12 @@ static int evict_merge_launch(const ems_params* p, int similarity, const void* k
     a.k = k; a.v = v; a.imp_idx = imp_idx; a.tbm_idx = tbm_idx;
     a.k_out = k_out; a.v_out = v_out; a.kept_pos = kept_pos;
     a.tbm_dest = tbm_dest; a.tbm_sim = tbm_sim;
-    a.k_norm = k_norm_opt ? k_norm_opt : static_cast<float*>(ws);
+    const MergePlan plan = plan_merge(p);
+    char* w = static_cast<char*>(ws);
+    a.k_norm = k_norm_opt ? k_norm_opt : reinterpret_cast<float*>(w + plan.off_norm);
+    a.slice_rows = plan.slice_rows; a.n_slices = plan.n_slices;
+    a.part_best = reinterpret_cast<float*>(w + plan.off_best);
+    a.part_arg = reinterpret_cast<int32_t*>(w + plan.off_arg);
     a.slot_count = slot_count;
     a.bkv = p->batch * p->kv_heads; a.head_dim = p->head_dim; a.seq_len = p->seq_len;
     a.window = p->window; a.budget = p->budget; a.n_imp = n_imp; a.n_tbm = n_tbm;

@@ -62,6 +62,10 @@ struct MergeArgs {
     float tau;
     const float* weight;  // [B*Hkv, seq_len] per-token merge weight, or null = plain mean
     int similarity;       // 0 key cosine, 1 value cosine, 2 their product
+    // centre slices of the destination search (dest_slicing); with one slice the partials are unused
+    int slice_rows, n_slices;
+    float* part_best;     // [B*Hkv, n_slices, n_tbm] best similarity within the slice
+    int32_t* part_arg;    // [B*Hkv, n_slices, n_tbm] its centre
 };
 
 struct ExpandArgs {
@@ -145,5 +149,6 @@ hipError_t launch_score_pass1(const ScoreArgs& a, bool f32, hipStream_t st);   /
 hipError_t launch_score_pass2(const ScoreArgs& a, bool f32, hipStream_t st);   // column sums
 hipError_t launch_select(const SelectArgs& a, hipStream_t st);
 hipError_t launch_evict_merge(const MergeArgs& a, bool f32, hipStream_t st);
+void dest_slicing(int n_imp, bool f32, int* slice_rows, int* n_slices);
 
 }  // namespace ems

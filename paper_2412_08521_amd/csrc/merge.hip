@@ -1,14 +1,16 @@
 // Head-wise evict-then-merge (Sec. 4.2, Eq. 5, App. A).
 //
-// dest_kernel   for every to-be-merged (TBM) token: cosine similarity of its key with
-//               every class-centre key as an MFMA contraction of the raw keys, scaled by
-//               the reciprocal norms afterwards, with the row arg-max fused into the
-//               accumulator read-out; similarity not above tau -> zero class.
-// merge_kernel  one wave per output row: a centre slot gathers the TBM tokens sent to it
-//               in ascending order and averages (unit keys scaled by the centre's norm,
-//               raw values); one block per head does the same for the zero class; the
-//               local-window rows are copied.  Every output element has exactly one
-//               writer, so there are no atomics and results are reproducible bit for bit.
+// dest_kernel     for every to-be-merged (TBM) token: cosine similarity of its key with
+//                 the class-centre keys as an MFMA contraction of the raw keys, scaled by
+//                 the reciprocal norms afterwards, with the row arg-max fused into the
+//                 accumulator read-out; similarity not above tau -> zero class.  With many
+//                 centres the centre list is cut into slices, one block per (128 tokens,
+//                 slice), and dest_combine_kernel takes the best slice per token.
+// merge_kernel    one wave per output row: a centre slot gathers the TBM tokens sent to it
+//                 in ascending order and averages (unit keys scaled by the centre's norm,
+//                 raw values); one block per head does the same for the zero class; the
+//                 local-window rows are copied.  Every output element has exactly one
+//                 writer, so there are no atomics and results are reproducible bit for bit.
 #include "ems_common.h"
 #include "ems_kernels.h"
 #include "ems_rows.h"
@@ -17,6 +19,11 @@ namespace ems {
 
 constexpr int kMrgWaves = 4;
 constexpr int kMrgBlock = kMrgWaves * kWave;
+constexpr int kDestDepth = 4;        // centre stages whose rows a block has in flight at once
+constexpr int kDestMaxSlices = 16;   // centre slices per head at most
+constexpr int kMergeWaves = 8;       // output rows per merge block
+constexpr int kMergeBlock = kMergeWaves * kWave;
+constexpr int kMergePiece = 4096;    // TBM tokens whose destinations a merge block holds in LDS
 
 template <typename T> struct DestCfg { static constexpr int kStageRows = 64; };
 template <> struct DestCfg<float> { static constexpr int kStageRows = 32; };
@@ -45,7 +52,8 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
     __shared__ __attribute__((aligned(16))) float lds_rn[kSrc][kStageRows];
 
     const int N = a.seq_len, n_imp = a.n_imp, n_tbm = a.n_tbm;
-    const int bkv = blockIdx.y;
+    const int bkv = blockIdx.z, slice = blockIdx.y;
+    const int c_begin = slice * a.slice_rows, c_end = min(n_imp, c_begin + a.slice_rows);   // this block's centres
     const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
     const T* V = reinterpret_cast<const T*>(a.v) + ((size_t)bkv * N) * D;
     const T* src[kSrc];
@@ -86,75 +94,73 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
     float best = -INFINITY;
     int arg = 0;
 
-    // Centre rows are gathered one stage ahead into registers (and their positions two stages
-    // ahead), so the global round trips run under the previous stage's MFMAs.
-    int pos_pf[kPerThread];
-    frag_t pf[kSrc][kPerThread];
-    auto load_pos = [&](int c0) {
+    // A round is kDestDepth stages of kStageRows centres.  All of a round's centre positions,
+    // then all of its rows, are requested before the first stage is used: two global round
+    // trips per round, however many stages it has.
+    for (int r0 = c_begin; r0 < c_end; r0 += kDestDepth * kStageRows) {
+        int pos_pf[kDestDepth][kPerThread];
+        frag_t pf[kDestDepth][kSrc][kPerThread];
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int ci = c0 + (threadIdx.x + i * kMrgBlock) / kCpr;
-            pos_pf[i] = ci < n_imp ? clamp_pos(imp[ci], N) : -1;
-        }
-    };
-    auto load_rows = [&]() {
+        for (int st = 0; st < kDestDepth; ++st)
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int cc = (threadIdx.x + i * kMrgBlock) % kCpr;
-#pragma unroll
-            for (int s = 0; s < kSrc; ++s)
-                pf[s][i] = load_frag_or_zero(src[s], ((size_t)max(pos_pf[i], 0) * kCpr + cc) * 16, pos_pf[i] >= 0);
-        }
-    };
-    load_pos(0);
-    load_rows();
-    load_pos(kStageRows);
-
-    for (int c0 = 0; c0 < n_imp; c0 += kStageRows) {
-        __syncthreads();                                   // previous tile fully consumed
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int c = threadIdx.x + i * kMrgBlock;
-            const int row = c / kCpr, cc = c % kCpr;
-#pragma unroll
-            for (int s = 0; s < kSrc; ++s) {
-                *reinterpret_cast<frag_t*>(lds[s] + row * kStride + cc * 16) = pf[s][i];
-                // the kCpr consecutive lanes that hold one row add up its squares
-                const float ss = group_sum<kCpr>(frag_sumsq<T>(pf[s][i]));
-                if (cc == 0) lds_rn[s][row] = inv_norm(ss);
-            }
-        }
-        __syncthreads();
-        if (c0 + kStageRows < n_imp) {                     // block-uniform
-            load_rows();
-            load_pos(c0 + 2 * kStageRows);
-        }
-#pragma unroll
-        for (int rs = 0; rs < kStageRows / 32; ++rs) {
-            const int cbase = c0 + rs * 32;
-            if (cbase >= n_imp) continue;                  // block-uniform
-            f32x16_t acc[kSrc];
-#pragma unroll
-            for (int s = 0; s < kSrc; ++s) {
-                acc[s] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int f = 0; f < kFrags; ++f) {
-                    const frag_t ac = *reinterpret_cast<const frag_t*>(lds[s] + (rs * 32 + col) * kStride + f * 32 + half * 16);
-                    mma<T>(acc[s], ac, bt[s][f]);
-                }
+            for (int i = 0; i < kPerThread; ++i) {
+                const int ci = r0 + st * kStageRows + (threadIdx.x + i * kMrgBlock) / kCpr;
+                pos_pf[st][i] = ci < c_end ? clamp_pos(imp[ci], N) : -1;
             }
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                f32x4_t rn[kSrc];
+        for (int st = 0; st < kDestDepth; ++st)
+#pragma unroll
+            for (int i = 0; i < kPerThread; ++i) {
+                const int cc = (threadIdx.x + i * kMrgBlock) % kCpr;
 #pragma unroll
                 for (int s = 0; s < kSrc; ++s)
-                    rn[s] = *reinterpret_cast<const f32x4_t*>(lds_rn[s] + rs * 32 + 8 * q4 + 4 * half);
+                    pf[st][s][i] = load_frag_or_zero(src[s], ((size_t)max(pos_pf[st][i], 0) * kCpr + cc) * 16, pos_pf[st][i] >= 0);
+            }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int ci = cbase + 8 * q4 + 4 * half + e;
-                    float sim = (acc[0][4 * q4 + e] * rn[0][e]) * t_rn[0];
-                    if constexpr (kSrc == 2) sim *= (acc[1][4 * q4 + e] * rn[1][e]) * t_rn[1];
-                    if (ci < n_imp && sim > best) { best = sim; arg = ci; }
+        for (int st = 0; st < kDestDepth; ++st) {
+            const int c0 = r0 + st * kStageRows;
+            if (c0 >= c_end) break;                            // block-uniform
+            __syncthreads();                                   // previous tile fully consumed
+#pragma unroll
+            for (int i = 0; i < kPerThread; ++i) {
+                const int c = threadIdx.x + i * kMrgBlock;
+                const int row = c / kCpr, cc = c % kCpr;
+#pragma unroll
+                for (int s = 0; s < kSrc; ++s) {
+                    *reinterpret_cast<frag_t*>(lds[s] + row * kStride + cc * 16) = pf[st][s][i];
+                    // the kCpr consecutive lanes that hold one row add up its squares
+                    const float ss = group_sum<kCpr>(frag_sumsq<T>(pf[st][s][i]));
+                    if (cc == 0) lds_rn[s][row] = inv_norm(ss);
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int rs = 0; rs < kStageRows / 32; ++rs) {
+                const int cbase = c0 + rs * 32;
+                if (cbase >= c_end) continue;                  // block-uniform
+                f32x16_t acc[kSrc];
+#pragma unroll
+                for (int s = 0; s < kSrc; ++s) {
+                    acc[s] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int f = 0; f < kFrags; ++f) {
+                        const frag_t ac = *reinterpret_cast<const frag_t*>(lds[s] + (rs * 32 + col) * kStride + f * 32 + half * 16);
+                        mma<T>(acc[s], ac, bt[s][f]);
+                    }
+                }
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4_t rn[kSrc];
+#pragma unroll
+                    for (int s = 0; s < kSrc; ++s)
+                        rn[s] = *reinterpret_cast<const f32x4_t*>(lds_rn[s] + rs * 32 + 8 * q4 + 4 * half);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int ci = cbase + 8 * q4 + 4 * half + e;
+                        float sim = (acc[0][4 * q4 + e] * rn[0][e]) * t_rn[0];
+                        if constexpr (kSrc == 2) sim *= (acc[1][4 * q4 + e] * rn[1][e]) * t_rn[1];
+                        if (ci < c_end && sim > best) { best = sim; arg = ci; }
+                    }
                 }
             }
         }
@@ -164,10 +170,40 @@ __global__ __launch_bounds__(kMrgBlock) void dest_kernel(MergeArgs a)
     const int arg_o = __shfl_xor(arg, 32);
     if (best_o > best || (best_o == best && arg_o < arg)) { best = best_o; arg = arg_o; }
     if (half == 0 && t_ok) {
-        a.tbm_sim[(size_t)bkv * n_tbm + ti] = best;
-        a.tbm_dest[(size_t)bkv * n_tbm + ti] = best > a.tau ? arg : a.budget;
-        a.k_norm[(size_t)bkv * (n_imp + n_tbm) + n_imp + ti] = sqrtf(k_sumsq);
+        if (a.n_slices == 1) {
+            a.tbm_sim[(size_t)bkv * n_tbm + ti] = best;
+            a.tbm_dest[(size_t)bkv * n_tbm + ti] = best > a.tau ? arg : a.budget;
+        } else {
+            a.part_best[((size_t)bkv * a.n_slices + slice) * n_tbm + ti] = best;
+            a.part_arg[((size_t)bkv * a.n_slices + slice) * n_tbm + ti] = arg;
+        }
+        if (slice == 0) a.k_norm[(size_t)bkv * (n_imp + n_tbm) + n_imp + ti] = sqrtf(k_sumsq);
     }
+}
+
+// The best slice of every TBM token (lowest slice, hence lowest centre, on ties), then the
+// threshold.  One thread per token.
+__global__ __launch_bounds__(kMrgBlock) void dest_combine_kernel(MergeArgs a)
+{
+    const int bkv = blockIdx.y, ti = blockIdx.x * kMrgBlock + threadIdx.x;
+    if (ti >= a.n_tbm) return;
+    const float* pb = a.part_best + (size_t)bkv * a.n_slices * a.n_tbm + ti;
+    const int32_t* pa = a.part_arg + (size_t)bkv * a.n_slices * a.n_tbm + ti;
+    float b[kDestMaxSlices];
+    int g[kDestMaxSlices];
+#pragma unroll
+    for (int s = 0; s < kDestMaxSlices; ++s) {               // every slice requested before the first compare
+        const bool on = s < a.n_slices;
+        b[s] = on ? pb[(size_t)s * a.n_tbm] : -INFINITY;
+        g[s] = on ? pa[(size_t)s * a.n_tbm] : 0;
+    }
+    float best = -INFINITY;
+    int arg = 0;
+#pragma unroll
+    for (int s = 0; s < kDestMaxSlices; ++s)
+        if (b[s] > best) { best = b[s]; arg = g[s]; }
+    a.tbm_sim[(size_t)bkv * a.n_tbm + ti] = best;
+    a.tbm_dest[(size_t)bkv * a.n_tbm + ti] = best > a.tau ? arg : a.budget;
 }
 
 // ------------------------------------------------------------------------------------
@@ -239,25 +275,26 @@ struct RowAcc {
     }
 };
 
-// Walks the TBM tokens of chunks `first, first+step, ...` (64 tokens each) whose
-// destination is `target` and adds them to `acc`; returns how many there were.
+// Walks the staged TBM tokens (`len` of them: destination and position in LDS) in chunks
+// `first, first+step, ...` of 64, adds those whose destination is `target` to `acc` and
+// returns how many there were.
 template <typename T, int D, bool kWeighted>
-__device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const MergeArgs& a, const T* K, const T* V,
-                                              const float* Wt, const int32_t* tbm, const int32_t* dest, int target,
+__device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const T* K, const T* V, const float* Wt,
+                                              const int* ldest, const int* lpos, int len, int target,
                                               int first, int step, int* wlist)
 {
     constexpr int kLpr = RowAcc<T, D>::kLpr, kGroups = RowAcc<T, D>::kGroups;
     const int lane = threadIdx.x % kWave;
     const int grp = lane / kLpr, piece = lane % kLpr;
-    const int n_chunks = (a.n_tbm + kWave - 1) / kWave;
+    const int n_chunks = (len + kWave - 1) / kWave;
     int count = 0;
     for (int ch = first; ch < n_chunks; ch += step) {
         const int i = ch * kWave + lane;
-        const bool match = i < a.n_tbm && dest[i] == target;
+        const bool match = i < len && ldest[i] == target;
         const unsigned long long mask = __ballot(match);
         if (mask == 0ull) continue;                              // wave-uniform
         const int n = __popcll(mask);
-        if (match) wlist[__popcll(mask & ((1ull << lane) - 1ull))] = clamp_pos(tbm[i], a.seq_len);
+        if (match) wlist[__popcll(mask & ((1ull << lane) - 1ull))] = lpos[i];
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         // kInFlight members per lane group at a time, all their loads issued before the first is
@@ -288,15 +325,18 @@ __device__ __forceinline__ int gather_members(RowAcc<T, D>& acc, const MergeArgs
 }
 
 template <typename T, int D, bool kWeighted>
-__global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
+__global__ __launch_bounds__(kMergeBlock) void merge_kernel(MergeArgs a)
 {
     using Acc = RowAcc<T, D>;
     constexpr int kE = Acc::kE, kLpr = Acc::kLpr;
 
-    __shared__ int wlist_all[kMrgWaves][kWave];
-    __shared__ float zsum[kMrgWaves][2][D];
-    __shared__ int zcnt[kMrgWaves];
-    __shared__ float zwsum[kMrgWaves];
+    // destinations and positions of a piece of the TBM list, shared by the block's rows
+    __shared__ int ldest[kMergePiece];
+    __shared__ int lpos[kMergePiece];
+    __shared__ int wlist_all[kMergeWaves][kWave];
+    __shared__ float zsum[kMergeWaves][2][D];
+    __shared__ int zcnt[kMergeWaves];
+    __shared__ float zwsum[kMergeWaves];
 
     const int N = a.seq_len, W = a.window, Nb = a.budget, n_imp = a.n_imp, n_tbm = a.n_tbm;
     const int bkv = blockIdx.y;
@@ -315,44 +355,16 @@ __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
     const int grp = lane / kLpr, piece = lane % kLpr;
     int* wlist = wlist_all[wave];
 
-    if (blockIdx.x == 0) {
-        // ---- zero class: the four waves split the TBM list, wave 0 adds them in order
-        Acc acc; acc.clear();
-        const int n = gather_members<T, D, kWeighted>(acc, a, K, V, Wt, tbm, dest, Nb, wave, kMrgWaves, wlist);
-        acc.template reduce_groups<kWeighted>();
-        if (grp == 0) {
-#pragma unroll
-            for (int i = 0; i < kE; ++i) { zsum[wave][0][piece * kE + i] = acc.k[i]; zsum[wave][1][piece * kE + i] = acc.v[i]; }
-        }
-        if (lane == 0) { zcnt[wave] = n; zwsum[wave] = acc.wsum; }
-        __syncthreads();
-        if (wave == 0 && grp == 0) {
-            int total = 0;
-            float wtot = 0.f;
-            for (int w = 0; w < kMrgWaves; ++w) { total += zcnt[w]; wtot += zwsum[w]; }
-            const float denom = kWeighted ? wtot : (float)total;     // members, or their total weight
-            float ok[kE], ov[kE];
-#pragma unroll
-            for (int i = 0; i < kE; ++i) {
-                float sk = 0.f, sv = 0.f;
-                for (int w = 0; w < kMrgWaves; ++w) { sk += zsum[w][0][piece * kE + i]; sv += zsum[w][1][piece * kE + i]; }
-                ok[i] = denom > 0.f ? sk / denom : 0.f;
-                ov[i] = denom > 0.f ? sv / denom : 0.f;
-            }
-            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ok);
-            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ov);
-            if (lane == 0) cnt[n_imp] = total;
-        }
-        return;
-    }
+    // what this wave produces: block 0 is the zero class (its waves split the TBM list), every
+    // other wave owns one output row: a class-centre slot, a local-window row, or nothing
+    const bool zero_class = blockIdx.x == 0;
+    const int job = zero_class ? -1 : (blockIdx.x - 1) * kMergeWaves + wave;     // wave-uniform
+    const bool centre = !zero_class && job < n_imp;
+    const bool local = !zero_class && job >= n_imp && job < n_imp + W;
 
-    const int job = (blockIdx.x - 1) * kMrgWaves + wave;          // wave-uniform
-    if (job >= n_imp + W) return;
-
-    if (job >= n_imp) {
+    if (local) {
         // ---- local-window row: copied unchanged
-        const int t = job - n_imp;
-        const int pos = N - W + t;
+        const int pos = N - W + (job - n_imp);
         if (grp == 0) {
             const frag_t fk = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)pos * kLpr + piece) * 16);
             const frag_t fv = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)pos * kLpr + piece) * 16);
@@ -360,40 +372,87 @@ __global__ __launch_bounds__(kMrgBlock) void merge_kernel(MergeArgs a)
             *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)job * kLpr + piece) * 16) = fv;
         }
         if (lane == 0) kept[job] = pos;
-        return;
     }
 
-    // ---- class-centre slot
-    const int c_pos = clamp_pos(imp[job], N);
+    // ---- class-centre slot: the centre itself is the first member
     Acc acc; acc.clear();
+    int c_pos = 0;
     float c_norm = 0.f;
     frag_t raw_k = zero_frag(), raw_v = zero_frag();
-    if (grp == 0) {
-        raw_k = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)c_pos * kLpr + piece) * 16);
-        raw_v = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)c_pos * kLpr + piece) * 16);
-        if constexpr (kWeighted) c_norm = acc.add_weighted(K, V, c_pos, piece, fmaxf(Wt[c_pos], 0.f));
-        else c_norm = acc.add(K, V, c_pos, piece);
+    if (centre) {
+        c_pos = clamp_pos(imp[job], N);
+        if (grp == 0) {
+            raw_k = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(K) + ((size_t)c_pos * kLpr + piece) * 16);
+            raw_v = *reinterpret_cast<const frag_t*>(reinterpret_cast<const char*>(V) + ((size_t)c_pos * kLpr + piece) * 16);
+            if constexpr (kWeighted) c_norm = acc.accumulate_weighted(raw_k, raw_v, fmaxf(Wt[c_pos], 0.f));
+            else c_norm = acc.accumulate(raw_k, raw_v);
+        }
+        c_norm = __shfl(c_norm, 0);
     }
-    c_norm = __shfl(c_norm, 0);
-    const int members = 1 + gather_members<T, D, kWeighted>(acc, a, K, V, Wt, tbm, dest, job, 0, 1, wlist);
-    acc.template reduce_groups<kWeighted>();
-    if (grp == 0) {
-        frag_t out_k = raw_k, out_v = raw_v;                      // nobody joined: exact copy
-        const float m = kWeighted ? acc.wsum : (float)members;    // total weight of the entry
-        if (members > 1 && m > 0.f) {
+
+    // ---- the TBM list goes through LDS a piece at a time; every wave takes its members from it
+    int joined = 0;
+    for (int p0 = 0; p0 < n_tbm; p0 += kMergePiece) {
+        const int len = min(kMergePiece, n_tbm - p0);
+        if (p0 > 0) __syncthreads();                       // the previous piece is consumed
+        for (int i = threadIdx.x; i < len; i += kMergeBlock) {
+            ldest[i] = dest[p0 + i];
+            lpos[i] = clamp_pos(tbm[p0 + i], N);
+        }
+        __syncthreads();
+        if (centre) joined += gather_members<T, D, kWeighted>(acc, K, V, Wt, ldest, lpos, len, job, 0, 1, wlist);
+        else if (zero_class) joined += gather_members<T, D, kWeighted>(acc, K, V, Wt, ldest, lpos, len, Nb, wave, kMergeWaves, wlist);
+    }
+
+    if (centre) {
+        const int members = 1 + joined;
+        acc.template reduce_groups<kWeighted>();
+        if (grp == 0) {
+            frag_t out_k = raw_k, out_v = raw_v;                      // nobody joined: exact copy
+            const float m = kWeighted ? acc.wsum : (float)members;    // total weight of the entry
+            if (members > 1 && m > 0.f) {
+                float ok[kE], ov[kE];
+#pragma unroll
+                for (int i = 0; i < kE; ++i) { ok[i] = c_norm * (acc.k[i] / m); ov[i] = acc.v[i] / m; }
+                out_k = Pack<T>::pack(ok);
+                out_v = Pack<T>::pack(ov);
+            }
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)job * kLpr + piece) * 16) = out_k;
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)job * kLpr + piece) * 16) = out_v;
+        }
+        if (lane == 0) {
+            kept[job] = c_pos;
+            cnt[job] = members;
+            a.k_norm[(size_t)bkv * (n_imp + n_tbm) + job] = c_norm;
+        }
+    }
+
+    if (zero_class) {
+        // ---- zero class: every wave has added its share in order; wave 0 adds the waves in order
+        acc.template reduce_groups<kWeighted>();
+        if (grp == 0) {
+#pragma unroll
+            for (int i = 0; i < kE; ++i) { zsum[wave][0][piece * kE + i] = acc.k[i]; zsum[wave][1][piece * kE + i] = acc.v[i]; }
+        }
+        if (lane == 0) { zcnt[wave] = joined; zwsum[wave] = acc.wsum; }
+        __syncthreads();
+        if (wave == 0 && grp == 0) {
+            int total = 0;
+            float wtot = 0.f;
+            for (int w = 0; w < kMergeWaves; ++w) { total += zcnt[w]; wtot += zwsum[w]; }
+            const float denom = kWeighted ? wtot : (float)total;     // members, or their total weight
             float ok[kE], ov[kE];
 #pragma unroll
-            for (int i = 0; i < kE; ++i) { ok[i] = c_norm * (acc.k[i] / m); ov[i] = acc.v[i] / m; }
-            out_k = Pack<T>::pack(ok);
-            out_v = Pack<T>::pack(ov);
+            for (int i = 0; i < kE; ++i) {
+                float sk = 0.f, sv = 0.f;
+                for (int w = 0; w < kMergeWaves; ++w) { sk += zsum[w][0][piece * kE + i]; sv += zsum[w][1][piece * kE + i]; }
+                ok[i] = denom > 0.f ? sk / denom : 0.f;
+                ov[i] = denom > 0.f ? sv / denom : 0.f;
+            }
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ok);
+            *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)Nb * kLpr + piece) * 16) = Pack<T>::pack(ov);
+            if (lane == 0) cnt[n_imp] = total;
         }
-        *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Ko) + ((size_t)job * kLpr + piece) * 16) = out_k;
-        *reinterpret_cast<frag_t*>(reinterpret_cast<char*>(Vo) + ((size_t)job * kLpr + piece) * 16) = out_v;
-    }
-    if (lane == 0) {
-        kept[job] = c_pos;
-        cnt[job] = members;
-        a.k_norm[(size_t)bkv * (n_imp + n_tbm) + job] = c_norm;
     }
 }
 
@@ -474,22 +533,38 @@ hipError_t launch_expand(const ExpandArgs& a, bool f32, hipStream_t st)
     return launch_expand_t<bf16_t, 128>(a, st);
 }
 
+// How the centre list is cut for dest_kernel: rows per slice (whole rounds) and slices.
+void dest_slicing(int n_imp, bool f32, int* slice_rows, int* n_slices)
+{
+    const int round_rows = kDestDepth * (f32 ? DestCfg<float>::kStageRows : DestCfg<bf16_t>::kStageRows);
+    const int rounds = (max(n_imp, 1) + round_rows - 1) / round_rows;
+    const int per_slice = (rounds + kDestMaxSlices - 1) / kDestMaxSlices;
+    *slice_rows = per_slice * round_rows;
+    *n_slices = (rounds + per_slice - 1) / per_slice;
+}
+
 template <typename T, int D>
 static hipError_t launch_evict_merge_t(const MergeArgs& a, hipStream_t st)
 {
     hipError_t e = hipSuccess;
     if (a.n_tbm > 0) {
-        dim3 g((a.n_tbm + kMrgWaves * 32 - 1) / (kMrgWaves * 32), a.bkv);
+        dim3 g((a.n_tbm + kMrgWaves * 32 - 1) / (kMrgWaves * 32), a.n_slices, a.bkv);
         if (a.similarity == 0) hipLaunchKernelGGL((dest_kernel<T, D, 0>), g, dim3(kMrgBlock), 0, st, a);
         else if (a.similarity == 1) hipLaunchKernelGGL((dest_kernel<T, D, 1>), g, dim3(kMrgBlock), 0, st, a);
         else hipLaunchKernelGGL((dest_kernel<T, D, 2>), g, dim3(kMrgBlock), 0, st, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
+        if (a.n_slices > 1) {
+            dim3 gc((a.n_tbm + kMrgBlock - 1) / kMrgBlock, a.bkv);
+            hipLaunchKernelGGL(dest_combine_kernel, gc, dim3(kMrgBlock), 0, st, a);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
     }
     const int jobs = a.n_imp + a.window;
-    dim3 g(1 + (jobs + kMrgWaves - 1) / kMrgWaves, a.bkv);
-    if (a.weight) hipLaunchKernelGGL((merge_kernel<T, D, true>), g, dim3(kMrgBlock), 0, st, a);
-    else hipLaunchKernelGGL((merge_kernel<T, D, false>), g, dim3(kMrgBlock), 0, st, a);
+    dim3 g(1 + (jobs + kMergeWaves - 1) / kMergeWaves, a.bkv);
+    if (a.weight) hipLaunchKernelGGL((merge_kernel<T, D, true>), g, dim3(kMergeBlock), 0, st, a);
+    else hipLaunchKernelGGL((merge_kernel<T, D, false>), g, dim3(kMergeBlock), 0, st, a);
     return hipGetLastError();
 }
 

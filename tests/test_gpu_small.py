@@ -151,7 +151,9 @@ MERGE_SHAPES = [
     (1, 2, 64, 700, 16, 48, 1.5),
     (2, 2, 128, 1500, 32, 256, 0.5),
     (1, 3, 128, 4096, 64, 128, 3.0),
-    (1, 1, 128, 3000, 32, 512, 2.0),
+    (1, 1, 128, 3000, 32, 512, 2.0),       # centre list searched in 2 (bf16) / 4 (f32) slices
+    (1, 2, 128, 12000, 32, 1100, 5.0),     # 5 / 9 slices; 5500 to-be-merged tokens: two LDS pieces in the merge
+    (1, 1, 64, 9000, 16, 2300, 0.6),       # f32: 18 rounds of centres, two per slice
 ]
 
 
