@@ -169,9 +169,10 @@ def main():
              "ms_per_launch": round(ms_pass1, 4)}
 
     # ---- the machine's own ceilings in the same process (bench-only library): a loop of bf16
-    # MFMAs, 16 waves per compute unit, on constant operands and on random ones (random data
-    # toggles far more logic: the power limit then sets a lower clock, and that is the ceiling
-    # real inputs see), and a plain 16-byte vector copy of Q
+    # MFMAs, 16 waves per compute unit, on operands that are all 1.0, on constants that differ
+    # from lane to lane, and on random ones (the more bits toggle, the lower the clock the power
+    # limit allows: the random-operand figure is the ceiling real inputs see), and a plain
+    # 16-byte vector copy of Q
     from paper_2412_08521_amd import bench_probe
     sink = torch.empty(1024 * 256, dtype=torch.float32, device="cuda")
     ops = torch.randn(bench_probe.OPERAND_BYTES // 2, device="cuda").to(torch.bfloat16)
@@ -180,12 +181,15 @@ def main():
     probe_flops = 1024 * 4 * 2500 * 32 * 32768
     ms_mfma_const = timed(lambda: bench_probe.probe_mfma(1024, 2500, sink), 3)
     ms_mfma_rand = timed(lambda: bench_probe.probe_mfma(1024, 2500, sink, operands=ops), 3)
+    ones = torch.ones(bench_probe.OPERAND_BYTES // 2, device="cuda", dtype=torch.bfloat16)
+    ms_mfma_ones = timed(lambda: bench_probe.probe_mfma(1024, 2500, sink, operands=ones), 3)
     q_copy = torch.empty_like(q)
     bench_probe.probe_copy(q, q_copy)
     ms_copy = timed(lambda: bench_probe.probe_copy(q, q_copy), 5)
     copy_bytes = 2 * q.numel() * q.element_size()
     del q_copy
-    ceilings = {"mfma_bf16_tflops_constant_operands": round(probe_flops / (ms_mfma_const * 1e-3) / 1e12, 1),
+    ceilings = {"mfma_bf16_tflops_all_ones_operands": round(probe_flops / (ms_mfma_ones * 1e-3) / 1e12, 1),
+                "mfma_bf16_tflops_constant_operands": round(probe_flops / (ms_mfma_const * 1e-3) / 1e12, 1),
                 "mfma_bf16_tflops_random_operands": round(probe_flops / (ms_mfma_rand * 1e-3) / 1e12, 1),
                 "copy_gbps": round(copy_bytes / (ms_copy * 1e-3) / 1e9, 1)}
     log(f"measured ceilings: {ceilings}")

@@ -270,7 +270,7 @@ int ems_redundancy_rate(const ems_params* p, const void* k, const void* v,
                         float* rate, float* best, void* hip_stream);
 
 /*
- * Decode-time state of one layer's compressed cache (Sec. 3.2, decoding paragraph; Sec. 5
+ * Decode-time state of one layer's compressed cache (Sec. 3.3, decoding paragraph; Sec. 5
  * "Memory analysis": besides the budget-sized cache, one scalar per kept token for s_Glo,
  * s_Loc^past, s_Loc^cur, the key norm and the position look-up-table).  Every member is a
  * DEVICE pointer owned by the caller; T = N_imp + N_tbm + window tokens per head: the
@@ -310,7 +310,7 @@ typedef struct {
 int ems_decode_workspace_bytes(const ems_params* p, size_t* decode_ws);
 
 /*
- * Fills the table and the scalars of `state` from what the prefill path returned (Sec. 3.2:
+ * Fills the table and the scalars of `state` from what the prefill path returned (Sec. 3.3:
  * the prefill's s_Glo and s_Loc are stored for the generation; s_Loc is the first
  * s_Loc^past, s_Loc^cur starts at zero).  state->k_cache / v_cache must already hold
  * ems_evict_merge's k_out / v_out; they are read (window-row norms), not written.
@@ -324,7 +324,7 @@ int ems_decode_init(const ems_params* p, const float* s_glo, const float* s_loc,
                     const ems_decode_state* state, void* hip_stream);
 
 /*
- * One generated token (Sec. 3.2, decoding paragraph; App. A "Evict-then-Merge Details"),
+ * One generated token (Sec. 3.3, decoding paragraph; App. A "Evict-then-Merge Details"),
  * for all heads in one launch.  `step` = number of tokens generated before this one, or
  * EMS_STEP_FROM_STATE to take it from state->step_count (a device scalar, so that the same
  * recorded launch can be replayed for token after token); either way step_count is left at

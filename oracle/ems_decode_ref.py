@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY: plain numpy in fp64, one head at a time, steps in the 
 order.  Only the tests, the smoke check and the benchmark's cpu_baseline leg may import it;
 it shares no code with the HIP library.
 
-What the paper fixes (Sec. 3.2, decoding paragraph; App. A "Evict-then-Merge Details" and
+What the paper fixes (Sec. 3.3, decoding paragraph; App. A "Evict-then-Merge Details" and
 "Shared Entry Expansion"; Sec. 5 "Memory analysis"):
   * every kept token carries scalars: s_Glo, s_Loc^past, s_Loc^cur, its key norm, and its
     place in the position look-up-table;
@@ -53,7 +53,7 @@ def _sizes(n, window, budget, merge_ratio):
 def decode_init(seq_len, window, budget, merge_ratio, k_cache, v_cache, kept_pos, tbm_idx,
                 tbm_dest, k_norm, slot_count, s_glo, s_loc):
     """Table and scalars of ONE head from what the prefill compression returned for it.
-    s_glo, s_loc are the prefill's accumulated scores over all N positions (Sec. 3.2: they
+    s_glo, s_loc are the prefill's accumulated scores over all N positions (Sec. 3.3: they
     are stored for the generation; the prefill's local score is the first s_Loc^past)."""
     n_imp, n_tbm = _sizes(seq_len, window, budget, merge_ratio)
     E, W = n_imp + n_tbm, window
@@ -125,7 +125,7 @@ def decode_step(st, step, window, budget, tau, softmax_scale, q_new, k_new, v_ne
     attn /= attn.sum(1, keepdims=True)
     a = attn.sum(0)                                         # summed over the group
 
-    # 2. s_Glo and s_Loc^cur accumulate the new row (Sec. 3.2)
+    # 2. s_Glo and s_Loc^cur accumulate the new row (Sec. 3.3)
     st["tok_glo"][live] += a[:T][live]
     st["tok_cur"][live] += a[:T][live]
     new_glo = new_cur = a[T]
@@ -194,7 +194,7 @@ def decode_step(st, step, window, budget, tau, softmax_scale, q_new, k_new, v_ne
     st["tok_pos"][f], st["tok_row"][f], st["tok_norm"][f] = old["pos"], s_star, old["norm"]
     st["tok_glo"][f], st["tok_past"][f], st["tok_cur"][f] = old["glo"], old["past"], old["cur"]
 
-    # 7. window of scores: after L_win generated tokens cur becomes past (Sec. 3.2)
+    # 7. window of scores: after L_win generated tokens cur becomes past (Sec. 3.3)
     if (step + 1) % W == 0:
         st["tok_past"] = st["tok_cur"].copy()
         st["tok_cur"] = np.zeros(T)

@@ -1,4 +1,4 @@
-// Decode-time update of the compressed cache (Sec. 3.2, decoding paragraph; App. A,
+// Decode-time update of the compressed cache (Sec. 3.3, decoding paragraph; App. A,
 // "Evict-then-Merge Details").
 //
 // decode_init_kernel  builds the per-token table (position, cache row, key norm, s_Glo,
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     block_reduce<kWaves, G, false>(sum, vbuf);
 #pragma unroll
     for (int g = 0; g < G; ++g) sum[g] = 1.0f / sum[g];
-    // accumulate the row into s_Glo and s_Loc^cur (Sec. 3.2); the sums that Eq. 2 needs
+    // accumulate the row into s_Glo and s_Loc^cur (Sec. 3.3); the sums that Eq. 2 needs
     // (phase 4) are those of the updated scalars
     float tot2[2] = {0.f, 0.f};                              // sum of s_Glo, sum of s_Loc
     for (int j0 = tid; j0 < Tn; j0 += kBlock * kUnroll) {
@@ -643,7 +643,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     }
     __syncthreads();
 
-    // ---- phase 7: a full window of queries: s_Loc^cur becomes s_Loc^past (Sec. 3.2) ----
+    // ---- phase 7: a full window of queries: s_Loc^cur becomes s_Loc^past (Sec. 3.3) ----
     if ((step + 1) % W == 0) {
         for (int j = tid; j < Tn; j += kBlock) { tok_past[j] = tok_cur[j]; tok_cur[j] = 0.f; }
     }

@@ -1,4 +1,4 @@
-"""Pins for the decode-time oracle (Sec. 3.2 decoding paragraph; App. A "Evict-then-Merge
+"""Pins for the decode-time oracle (Sec. 3.3 decoding paragraph; App. A "Evict-then-Merge
 Details"): attention row against a dense softmax over the explicitly expanded cache, score
 bookkeeping, window ring, threshold extremes, entries as plain means of everything they
 absorbed (shadow bookkeeping on the raw tokens), table invariants."""
