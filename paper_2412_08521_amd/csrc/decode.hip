@@ -4,7 +4,8 @@
 // decode_init_kernel  builds the per-token table (position, cache row, key norm, s_Glo,
 //                     s_Loc^past, s_Loc^cur) from what the prefill compression returned.
 // decode_step_kernel  one generated token: one block per (batch, kv-head) runs the whole
-//                     step -- attention row of the new query over the expanded run-time
+//                     step (for large caches the two sweeps over the cache rows are their own
+//                     launches over row slices, see kPart) -- attention row of the new query over the expanded run-time
 //                     cache (one dot product per cache ROW, shared by the tokens that share
 //                     the entry; coalesced row loads, v_dot2 partials added with DPP),
 //                     score accumulation, window ring shift, least important centre, its
@@ -188,14 +189,38 @@ __global__ __launch_bounds__(256) void decode_init_kernel(DecodeInitArgs a)
 }
 
 // ------------------------------------------------------------------------------------
-// One block per (batch, kv-head); kBlock = 256 for small caches (the step is a chain of short
-// dependent phases, and every instruction a wave spends on a block-wide bookkeeping step is
-// paid once per wave), 1024 for large ones (more loads in flight).
+// kPart = 0: one block per (batch, kv-head) runs the whole step, kBlock = 256 (the step is a chain
+// of short dependent phases, and every instruction a wave spends on a block-wide bookkeeping
+// step is paid once per wave).
+// Large caches: one compute unit cannot pull the cache rows fast enough, so the step is four
+// launches in stream order, the two row sweeps cut into slices of a.slice_rows rows:
+//   kPart = 1  phase 1 (row dots)           grid (slices, heads), 256 threads
+//   kPart = 2  phases 2-4                    grid (1, heads), 1024 threads
+//   kPart = 3  phase 5 (centre cosines)      grid (slices, heads), 256 threads
+//   kPart = 4  phases 6-7                    grid (1, heads), 1024 threads
+// (Letting the last cosine block of a head run phases 6-7 itself saves a launch and was measured
+// slower: the next launch's latency hides behind the sweep anyway.)
+// What one part leaves for the next lives in the workspace: the staged dots and row norms, and a
+// small hand-over record per head (kHand* offsets below).
 // Dynamic LDS (floats): dot[G][budget] | rn[budget] when that fits, else the same arrays
 // live in the caller's workspace (a.lds_floats == 0).
-template <typename T, int D, int G, int kBlock>
+constexpr int kHandSelf = 0;       // [8]  new query . new key per q-head (log2 units)
+constexpr int kHandNewNorm = 8;    //      norm of the new key
+constexpr int kHandOldSc = 9;      // [4]  scalars of the token that left the window
+constexpr int kHandOldPos = 13;    //      its position (int)
+constexpr int kHandStar = 14;      //      the least important centre (int)
+constexpr int kHandStep = 15;      //      tokens generated before this one (int)
+constexpr int kHandPart = 16;      // [kDecodeMaxSlices][2] best cosine and its centre per slice
+constexpr int kHandOldRow = kHandPart + 2 * kDecodeMaxSlices;   // key row, then value row, of that token
+
+template <typename T, int D, int G, int kBlock, int kPart>
 __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
 {
+    constexpr bool kAll = kPart == 0;
+    constexpr bool kDoDots = kAll || kPart == 1, kDoSoftmax = kAll || kPart == 2;
+    constexpr bool kDoCos = kAll || kPart == 3;
+    static_assert(kPart >= 0 && kPart <= 4, "parts");
+    static_assert(kHandOldRow % 4 == 0 && kHandOldRow + 2 * D * (int)sizeof(T) / 4 <= kDecodeHandFloats, "hand-over record");
     using P = Pack<T>;
     constexpr int kE = P::kElems;
     constexpr int kWaves = kBlock / kWave;
@@ -204,7 +229,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     constexpr int kRowBytes = Tile<T, D>::kRowBytes;
     constexpr int kUnroll = 4;                               // independent loads in flight per thread
     constexpr int kPre = kBlock == 256 ? 2 : 1;              // row tiles in flight per wave
-    constexpr bool kPreload = kBlock == 256;                 // first batch of table elements fetched up front
+    constexpr bool kPreload = (kAll && kBlock == 256) || kPart == 2;   // first batch of table elements fetched up front
 
     extern __shared__ float dyn_lds[];
     __shared__ float fbuf[kWaves];
@@ -219,11 +244,14 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
 
     const int n_imp = a.n_imp, E = a.n_imp + a.n_tbm, W = a.window, Nb = a.budget;
     const int Tn = E + W;
-    const int bkv = blockIdx.x;
+    const int bkv = blockIdx.y, slice = blockIdx.x;          // slice = 0 unless the part sweeps rows
     const int tid = threadIdx.x;
-    // tokens generated before this one: the caller's count, or the counter kept in the state
-    // (which is advanced by a separate launch after this kernel, so every block reads the same)
-    const int step = a.step >= 0 ? a.step : *a.st.step_count;
+    // tokens generated before this one: the caller's count, or the counter kept in the state.  The
+    // counter is advanced after every block has read it: by a separate launch after the one-launch
+    // step; in the sliced step the first part copies it into every head's hand-over record,
+    // the later parts read that copy, and the last part advances it.
+    const int step = a.step >= 0 ? a.step
+                   : (kPart >= 2 ? reinterpret_cast<const int*>(a.hand + (size_t)bkv * kDecodeHandFloats)[kHandStep] : *a.st.step_count);
     const int lane = tid % kWave, wave = tid / kWave;
     const int col = lane & 31, half = lane >> 5;             // MFMA operand row / k-half of this lane
     const int grp = tid / kLpr, piece = tid % kLpr;
@@ -239,8 +267,18 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     float* tok_glo = a.st.tok_glo + (size_t)bkv * Tn;
     float* tok_past = a.st.tok_past + (size_t)bkv * Tn;
     float* tok_cur = a.st.tok_cur + (size_t)bkv * Tn;
-    const bool in_lds = a.lds_floats > 0;                    // block-uniform
-    float* stage = in_lds ? dyn_lds : a.ws + (size_t)bkv * ((size_t)(G + 1) * Nb);
+    // the sweeping parts write the staged arrays to the workspace; the part that consumes them
+    // copies them into LDS first when they fit
+    float* ws_stage = a.ws + (size_t)bkv * ((size_t)(G + 1) * Nb);
+    const bool in_lds = a.lds_floats > 0 && (kAll || kPart == 2);   // block-uniform
+    float* stage = in_lds ? dyn_lds : ws_stage;
+    float* hand = kAll ? nullptr : a.hand + (size_t)bkv * kDecodeHandFloats;
+    int* hand_i = reinterpret_cast<int*>(hand);
+    frag_t* hand_row = reinterpret_cast<frag_t*>(hand + kHandOldRow);
+    // rows of this block's sweeps: every row, or the block's slice
+    const int r_lo = kAll ? 0 : slice * a.slice_rows;
+    const int r_end = kAll ? Nb + 1 : min(r_lo + a.slice_rows, Nb + 1);       // phase 1 (row Nb = the new key)
+    const int c_end = kAll ? n_imp : min(r_lo + a.slice_rows, n_imp);        // phase 5
     float* dot = stage;                                      // [G][budget] q_g . cache row
     float* rn_of = stage + (size_t)G * Nb;                   // [budget] copy of row_norm
     const char* qn = reinterpret_cast<const char*>(a.q_new) + (size_t)bkv * G * D * sizeof(T);
@@ -263,8 +301,17 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     constexpr int kRowsPerPass = kWaves * kRowsPerWave;
     constexpr int kInFlight = kBlock == 1024 ? 8 : 4;        // row loads in flight per lane (bf16 path)
     const int sub = lane / kLpr;                             // this lane's row within the wave's load
-    const int ct_mine = tid < n_imp ? entry_tok[tid] : 0;    // used in phase 4
+    constexpr int kCt = kBlock == 1024 ? 2 : 1;              // centre tokens looked up ahead per thread (phase 4)
+    int ct_pre[kCt];
+#pragma unroll
+    for (int u = 0; u < kCt; ++u) ct_pre[u] = (kDoSoftmax && tid + u * kBlock < n_imp) ? entry_tok[tid + u * kBlock] : 0;
     frag_t new_k = zero_frag(), new_v = zero_frag();
+    float m[G], sum[G];
+    float tot2[2] = {0.f, 0.f};                              // sum of s_Glo, sum of s_Loc
+    float self_tot = 0.f;
+    int s_star = 0, f = 0;
+    float cv = 0.f;
+    int ci = -1;
     int pre_rr[kUnroll];
     float pre_tn[kUnroll], pre_tg[kUnroll], pre_tp[kUnroll], pre_tc[kUnroll];
     auto preload_table = [&]() {
@@ -279,6 +326,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
             pre_tc[u] = ok ? tok_cur[j] : 0.f;
         }
     };
+    if constexpr (kDoDots) {
     if constexpr (kDot2) {
         frag_t qp[G];
 #pragma unroll
@@ -292,17 +340,17 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
                 fk[u] = r < Nb ? *reinterpret_cast<const frag_t*>(Kc + ((size_t)r * kLpr + piece) * 16) : new_k;
             }
         };
-        const int r_first = wave * kRowsPerWave + sub;
+        const int r_first = r_lo + wave * kRowsPerWave + sub;
         load_rows(r_first);
         preload_table();
-        const float rn_mine = tid < Nb ? row_norm[tid] : 0.f;
+        const float rn_mine = (kAll && tid < Nb) ? row_norm[tid] : 0.f;
         if (grp == 0) new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
-        for (int r0 = r_first; r0 <= Nb; r0 += kRowsPerPass * kInFlight) {
+        for (int r0 = r_first; r0 < r_end; r0 += kRowsPerPass * kInFlight) {
             if (r0 != r_first) load_rows(r0);
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {
                 const int r = r0 + u * kRowsPerPass;
-                if (r > Nb) break;                           // uniform over the row's lanes
+                if (r >= r_end) break;                       // uniform over the row's lanes
                 float d[G];
 #pragma unroll
                 for (int g = 0; g < G; ++g) d[g] = group_sum<kLpr>(dot8_bf16(fk[u], qp[g]));
@@ -312,23 +360,25 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
                         for (int g = 0; g < G; ++g) dot[(size_t)g * Nb + r] = d[g];
                     } else {
 #pragma unroll
-                        for (int g = 0; g < G; ++g) sh_self[g] = a.scale_log2e * d[g];
+                        for (int g = 0; g < G; ++g) {
+                            sh_self[g] = a.scale_log2e * d[g];
+                            if (!kAll) hand[kHandSelf + g] = a.scale_log2e * d[g];
+                        }
                     }
                 }
             }
         }
-        if (tid < Nb) rn_of[tid] = rn_mine;
-        for (int r = tid + kBlock; r < Nb; r += kBlock) rn_of[r] = row_norm[r];
-        if (grp == 0) {
+        for (int r = r_lo + tid; r < min(r_end, Nb); r += kBlock) rn_of[r] = (kAll && r == tid) ? rn_mine : row_norm[r];
+        if (grp == 0 && (kAll || slice == 0)) {
             const float ss = group_sum<kLpr>(frag_sumsq<T>(new_k));
-            if (piece == 0) sh_newnorm = sqrtf(ss);
+            if (piece == 0) { sh_newnorm = sqrtf(ss); if (!kAll) hand[kHandNewNorm] = sqrtf(ss); }
         }
     } else {
         frag_t bq[kFrags];
 #pragma unroll
         for (int f = 0; f < kFrags; ++f)
             bq[f] = load_frag_or_zero(qn, (size_t)col * kRowBytes + f * 32 + half * 16, col < G);
-        const int n_tiles = (Nb + 1 + 31) / 32;
+        const int t_lo = r_lo / 32, n_tiles = (r_end + 31) / 32;      // slices are whole tiles
         frag_t fa[kPre][kFrags];
         auto load_tiles = [&](int t0) {
 #pragma unroll
@@ -339,15 +389,15 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
                 for (int f = 0; f < kFrags; ++f) fa[u][f] = load_frag_or_zero(src, f * 32 + half * 16, r <= Nb);
             }
         };
-        load_tiles(wave);
+        load_tiles(t_lo + wave);
         preload_table();
-        const float rn_mine = tid < Nb ? row_norm[tid] : 0.f;
+        const float rn_mine = (kAll && tid < Nb) ? row_norm[tid] : 0.f;
         if (grp == 0) {
             new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
             new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
         }
-        for (int t0 = wave; t0 < n_tiles; t0 += kWaves * kPre) {
-            if (t0 != wave) load_tiles(t0);
+        for (int t0 = t_lo + wave; t0 < n_tiles; t0 += kWaves * kPre) {
+            if (t0 != t_lo + wave) load_tiles(t0);
 #pragma unroll
             for (int u = 0; u < kPre; ++u) {
                 const int t = t0 + u * kWaves;
@@ -361,24 +411,52 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
                     for (int r16 = 0; r16 < 16; ++r16) {
                         const int row = t * 32 + acc_row(r16, half);
                         if (row < Nb) dot[(size_t)col * Nb + row] = acc[r16];
-                        else if (row == Nb) sh_self[col] = a.scale_log2e * acc[r16];
+                        else if (row == Nb) {
+                            sh_self[col] = a.scale_log2e * acc[r16];
+                            if (!kAll) hand[kHandSelf + col] = a.scale_log2e * acc[r16];
+                        }
                     }
                 }
             }
         }
-        if (tid < Nb) rn_of[tid] = rn_mine;
-        for (int r = tid + kBlock; r < Nb; r += kBlock) rn_of[r] = row_norm[r];
-        if (grp == 0) {
+        for (int r = r_lo + tid; r < min(r_end, Nb); r += kBlock) rn_of[r] = (kAll && r == tid) ? rn_mine : row_norm[r];
+        if (grp == 0 && (kAll || slice == 0)) {
             const float ss = group_sum<kLpr>(frag_sumsq<T>(new_k));
-            if (piece == 0) sh_newnorm = sqrtf(ss);
+            if (piece == 0) { sh_newnorm = sqrtf(ss); if (!kAll) hand[kHandNewNorm] = sqrtf(ss); }
         }
     }
+    }   // kDoDots
+    if constexpr (kPart == 1) {
+        if (slice == 0 && tid == 0) hand_i[kHandStep] = step;
+        return;
+    }
+    if constexpr (kPart == 2) {
+        // what the dots launch left: the new token's own logits and norm, the staged arrays
+        preload_table();
+        if (tid < G) sh_self[tid] = hand[kHandSelf + tid];
+        if (tid == 0) sh_newnorm = hand[kHandNewNorm];
+        if (grp == 0) {
+            new_k = *reinterpret_cast<const frag_t*>(kn + piece * 16);
+            new_v = *reinterpret_cast<const frag_t*>(vn + piece * 16);
+        }
+        if (in_lds) {
+            constexpr int kCopy = 8;                         // loads in flight per thread
+            for (int i0 = tid; i0 < (G + 1) * Nb; i0 += kBlock * kCopy) {
+                float t[kCopy];
+#pragma unroll
+                for (int u = 0; u < kCopy; ++u) t[u] = i0 + u * kBlock < (G + 1) * Nb ? ws_stage[i0 + u * kBlock] : 0.f;
+#pragma unroll
+                for (int u = 0; u < kCopy; ++u)
+                    if (i0 + u * kBlock < (G + 1) * Nb) dyn_lds[i0 + u * kBlock] = t[u];
+            }
+        }
+    }
+    if constexpr (kDoSoftmax) {
     __syncthreads();
 
     // ---- phase 2: softmax over the live tokens and the new token (Eq. 1) ---------------
     // logit of token j in row r: scale * (|k_j| / |centre of r|) * (q . row r).  Three light
     // sweeps over the table: maxima, sums, weights.
-    float m[G], sum[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) m[g] = sh_self[g];
     for (int j0 = tid; j0 < Tn; j0 += kBlock * kUnroll) {
@@ -427,7 +505,6 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     for (int g = 0; g < G; ++g) sum[g] = 1.0f / sum[g];
     // accumulate the row into s_Glo and s_Loc^cur (Sec. 3.3); the sums that Eq. 2 needs
     // (phase 4) are those of the updated scalars
-    float tot2[2] = {0.f, 0.f};                              // sum of s_Glo, sum of s_Loc
     for (int j0 = tid; j0 < Tn; j0 += kBlock * kUnroll) {
         int rr[kUnroll];
         float tn[kUnroll], tg[kUnroll], tp[kUnroll], tc[kUnroll];
@@ -471,8 +548,7 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
             }
         }
     }
-    float self_tot = 0.f;                                    // every thread: same value
-#pragma unroll
+#pragma unroll                                               // self_tot: every thread, same value
     for (int g = 0; g < G; ++g) {
         const float w = exp2_fast(sh_self[g] - m[g]) * sum[g];
         self_tot += w;
@@ -502,37 +578,58 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     const float align = tot2[0] > 0.f ? tot2[1] / tot2[0] : 0.f;
     float bv = 0.f;
     int bi = -1;
-    for (int s = tid; s < n_imp; s += kBlock) {
-        const int ct = s == tid ? ct_mine : entry_tok[s];
-        const float sc = fmaxf(tok_glo[ct] * align, tok_past[ct] + tok_cur[ct]);
-        if (better<true>(sc, s, bv, bi)) { bv = sc; bi = s; }
+    for (int s0 = tid; s0 < n_imp; s0 += kBlock * kCt) {
+        float cg[kCt], cp[kCt], cc[kCt];
+#pragma unroll
+        for (int u = 0; u < kCt; ++u) {                      // every gather requested before the first is used
+            const int s = s0 + u * kBlock;
+            const int ct = s0 == tid ? ct_pre[u] : (s < n_imp ? entry_tok[s] : 0);
+            cg[u] = tok_glo[ct]; cp[u] = tok_past[ct]; cc[u] = tok_cur[ct];
+        }
+#pragma unroll
+        for (int u = 0; u < kCt; ++u) {
+            const int s = s0 + u * kBlock;
+            const float sc = fmaxf(cg[u] * align, cp[u] + cc[u]);
+            if (s < n_imp && better<true>(sc, s, bv, bi)) { bv = sc; bi = s; }
+        }
     }
     block_arg<kWaves, true>(bv, bi, fbuf, ibuf);             // its barriers also publish phase 3
-    const int s_star = max(bi, 0);                           // block-uniform, in [0, n_imp)
-    const int f = entry_tok[s_star];
+    s_star = max(bi, 0);                                     // block-uniform, in [0, n_imp)
+    }   // kDoSoftmax
+    if constexpr (kPart == 2) {
+        if (grp == 0) { hand_row[piece] = old_k[piece]; hand_row[kLpr + piece] = old_v[piece]; }
+        if (tid == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hand[kHandOldSc + i] = old_sc[i];
+            hand_i[kHandOldPos] = old_pos;
+            hand_i[kHandStar] = s_star;
+        }
+        return;
+    }
+    if constexpr (kPart >= 3) s_star = hand_i[kHandStar];
+    f = entry_tok[s_star];
 
     // ---- phase 5: its most similar other centre (Eq. 5, cosine of the stored keys) -----
     // bf16: per entry row the dot with the chosen row and the row's own squared norm, again as
     // v_dot2 partials added with DPP.  f32: two MFMA chains per tile of 32 entries -- tile x
     // (chosen row in every column) for the dots, tile x tile for the squared norms on its
     // diagonal.
-    float cv = 0.f;
-    int ci = -1;
+    if constexpr (kDoCos) {
     if constexpr (kDot2) {
         const frag_t sp = *reinterpret_cast<const frag_t*>(Kc + ((size_t)s_star * kLpr + piece) * 16);
         const float rn_star = inv_norm(group_sum<kLpr>(dot8_bf16(sp, sp)));
-        const int s_first = wave * kRowsPerWave + sub;
-        for (int s0 = s_first; s0 < n_imp; s0 += kRowsPerPass * kInFlight) {
+        const int s_first = r_lo + wave * kRowsPerWave + sub;
+        for (int s0 = s_first; s0 < c_end; s0 += kRowsPerPass * kInFlight) {
             frag_t fk[kInFlight];
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {
                 const int s = s0 + u * kRowsPerPass;
-                fk[u] = load_frag_or_zero(Kc, ((size_t)s * kLpr + piece) * 16, s < n_imp);
+                fk[u] = load_frag_or_zero(Kc, ((size_t)s * kLpr + piece) * 16, s < c_end);
             }
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {
                 const int s = s0 + u * kRowsPerPass;
-                if (s >= n_imp) break;                       // uniform over the row's lanes
+                if (s >= c_end) break;                       // uniform over the row's lanes
                 const float d = group_sum<kLpr>(dot8_bf16(fk[u], sp));
                 const float e2 = group_sum<kLpr>(dot8_bf16(fk[u], fk[u]));
                 const float sim = (d * inv_norm(e2)) * rn_star;
@@ -550,19 +647,19 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
         }
         ss += __shfl_xor(ss, 32);
         const float rn_star = inv_norm(ss);
-        const int n_tiles = (n_imp + 31) / 32;
+        const int t_lo = r_lo / 32, n_tiles = (c_end + 31) / 32;
         const int pick = col & 15;                           // the accumulator register this lane judges
         const int my_local = acc_row(pick, half);            // ... and the tile row it belongs to
         const bool diag_here = half == ((col >> 2) & 1);     // this lane holds |row col|^2 ...
         const int diag_reg = 4 * (col >> 3) + (col & 3);     // ... in this register
-        for (int t0 = wave; t0 < n_tiles; t0 += kWaves * kPre) {
+        for (int t0 = t_lo + wave; t0 < n_tiles; t0 += kWaves * kPre) {
             frag_t fa[kPre][kFrags];
 #pragma unroll
             for (int u = 0; u < kPre; ++u) {
                 const int r = (t0 + u * kWaves) * 32 + col;
 #pragma unroll
                 for (int fr = 0; fr < kFrags; ++fr)
-                    fa[u][fr] = load_frag_or_zero(Kc, (size_t)r * kRowBytes + fr * 32 + half * 16, r < n_imp);
+                    fa[u][fr] = load_frag_or_zero(Kc, (size_t)r * kRowBytes + fr * 32 + half * 16, r < c_end);
             }
 #pragma unroll
             for (int u = 0; u < kPre; ++u) {
@@ -580,11 +677,27 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 const int s = t * 32 + my_local;
                 const float sim = (acc_pick(acc, pick) * inv_norm(sq[wave][my_local])) * rn_star;
-                if (col < 16 && s < n_imp && s != s_star && better<false>(sim, s, cv, ci)) { cv = sim; ci = s; }
+                if (col < 16 && s < c_end && s != s_star && better<false>(sim, s, cv, ci)) { cv = sim; ci = s; }
             }
         }
     }
+    }   // kDoCos
+    if constexpr (kPart == 4) {
+        // the slices' winners (combined below, lowest centre on ties) and the token that left the window
+        cv = tid < a.n_slices ? hand[kHandPart + 2 * tid] : 0.f;
+        ci = tid < a.n_slices ? hand_i[kHandPart + 2 * tid + 1] : -1;
+        if (grp == 0) { old_k[piece] = hand_row[piece]; old_v[piece] = hand_row[kLpr + piece]; }
+        if (tid == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) old_sc[i] = hand[kHandOldSc + i];
+            old_pos = hand_i[kHandOldPos];
+        }
+    }
     block_arg<kWaves, false>(cv, ci, fbuf, ibuf);
+    if constexpr (kPart == 3) {
+        if (tid == 0) { hand[kHandPart + 2 * slice] = cv; hand_i[kHandPart + 2 * slice + 1] = ci; }
+        return;
+    }
     const bool merged = ci >= 0 && cv > a.tau;
     const int dst = merged ? ci : -1;
 
@@ -647,6 +760,9 @@ __global__ __launch_bounds__(kBlock) void decode_step_kernel(DecodeStepArgs a)
     if ((step + 1) % W == 0) {
         for (int j = tid; j < Tn; j += kBlock) { tok_past[j] = tok_cur[j]; tok_cur[j] = 0.f; }
     }
+    if constexpr (kPart == 4) {
+        if (bkv == 0 && tid == 0) *a.st.step_count = step + 1;   // every block of the step reads the hand-over copy
+    }
 }
 
 __global__ void decode_bump_kernel(int32_t* step_count, int step)
@@ -669,35 +785,55 @@ hipError_t launch_decode_init(const DecodeInitArgs& a, bool f32, hipStream_t st)
     return a.head_dim == 64 ? launch_decode_init_t<bf16_t, 64>(a, st) : launch_decode_init_t<bf16_t, 128>(a, st);
 }
 
-template <typename T, int D, int kBlock>
-static hipError_t launch_decode_step_b(const DecodeStepArgs& a, hipStream_t st)
+template <typename T, int D, int kBlock, int kPart>
+static hipError_t launch_decode_part(const DecodeStepArgs& a, hipStream_t st)
 {
-    const dim3 g(a.bkv), b(kBlock);
-    const size_t lds = sizeof(float) * (size_t)a.lds_floats;
+    const bool sweeps = kPart == 1 || kPart == 3;
+    const dim3 g(sweeps ? a.n_slices : 1, a.bkv), b(kBlock);
+    const size_t lds = (kPart == 0 || kPart == 2) ? sizeof(float) * (size_t)a.lds_floats : 0;
     switch (a.group) {
-        case 1: hipLaunchKernelGGL((decode_step_kernel<T, D, 1, kBlock>), g, b, lds, st, a); break;
-        case 2: hipLaunchKernelGGL((decode_step_kernel<T, D, 2, kBlock>), g, b, lds, st, a); break;
-        case 4: hipLaunchKernelGGL((decode_step_kernel<T, D, 4, kBlock>), g, b, lds, st, a); break;
-        case 8: hipLaunchKernelGGL((decode_step_kernel<T, D, 8, kBlock>), g, b, lds, st, a); break;
+        case 1: hipLaunchKernelGGL((decode_step_kernel<T, D, 1, kBlock, kPart>), g, b, lds, st, a); break;
+        case 2: hipLaunchKernelGGL((decode_step_kernel<T, D, 2, kBlock, kPart>), g, b, lds, st, a); break;
+        case 4: hipLaunchKernelGGL((decode_step_kernel<T, D, 4, kBlock, kPart>), g, b, lds, st, a); break;
+        case 8: hipLaunchKernelGGL((decode_step_kernel<T, D, 8, kBlock, kPart>), g, b, lds, st, a); break;
         default: return hipErrorInvalidValue;
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(decode_bump_kernel, dim3(1), dim3(1), 0, st, a.st.step_count, a.step);
     return hipGetLastError();
+}
+
+// Whether the step runs as four launches over row slices, and how the rows are cut.  f32 rows
+// need twice the operand registers: the validation mode always takes the one-block kernel.
+bool decode_split(int budget, int n_imp, int n_tbm, int window, bool f32, int* slice_rows, int* n_slices)
+{
+    *slice_rows = 0; *n_slices = 1;
+    if (f32 || (budget <= 512 && n_imp + n_tbm + window <= 2048)) return false;
+    const int tiles = (budget + 1 + 31) / 32;                     // 32-row tiles, the new key's row included
+    int per = 4;                                                  // 128 rows per slice ...
+    while ((tiles + per - 1) / per > kDecodeMaxSlices) per *= 2;  // ... unless that makes too many slices
+    *slice_rows = per * 32;
+    *n_slices = (tiles + per - 1) / per;
+    return true;
 }
 
 template <typename T, int D>
 static hipError_t launch_decode_step_t(const DecodeStepArgs& a, hipStream_t st)
 {
-    // f32 rows need twice the operand registers: the validation mode always takes the small block
-    if constexpr (sizeof(T) == 4) {
-        return launch_decode_step_b<T, D, 256>(a, st);
+    hipError_t e;
+    if (a.n_slices > 1 || a.slice_rows > 0) {
+        if constexpr (sizeof(T) == 2) {
+            e = launch_decode_part<T, D, 256, 1>(a, st);
+            if (e == hipSuccess) e = launch_decode_part<T, D, 1024, 2>(a, st);
+            if (e == hipSuccess) e = launch_decode_part<T, D, 256, 3>(a, st);
+            if (e == hipSuccess) e = launch_decode_part<T, D, 1024, 4>(a, st);
+        } else {
+            return hipErrorInvalidValue;
+        }
     } else {
-        const int Tn = a.n_imp + a.n_tbm + a.window;
-        if (a.budget <= 512 && Tn <= 2048) return launch_decode_step_b<T, D, 256>(a, st);
-        return launch_decode_step_b<T, D, 1024>(a, st);
+        e = launch_decode_part<T, D, 256, 0>(a, st);
     }
+    if (e != hipSuccess || a.slice_rows > 0) return e;           // the sliced step advances the counter itself
+    hipLaunchKernelGGL(decode_bump_kernel, dim3(1), dim3(1), 0, st, a.st.step_count, a.step);
+    return hipGetLastError();
 }
 
 hipError_t launch_decode_step(const DecodeStepArgs& a, bool f32, hipStream_t st)

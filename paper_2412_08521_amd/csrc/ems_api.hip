@@ -464,11 +464,22 @@ static bool decode_params_ok(const ems_params* p, int* why)
     return g == 1 || g == 2 || g == 4 || g == 8;
 }
 
-static size_t decode_ws_bytes(const ems_params* p)
+// Decode-step workspace: the staged row dots and row norms, then (large caches) the hand-over
+// records of the sliced step.
+static size_t decode_stage_bytes(const ems_params* p)
 {
     const size_t bkv = (size_t)p->batch * p->kv_heads;
     const size_t g = (size_t)(p->q_heads / p->kv_heads);
     return align_up(sizeof(float) * bkv * (g + 1) * (size_t)p->budget);
+}
+
+static size_t decode_ws_bytes(const ems_params* p)
+{
+    int n_imp, n_tbm, slice_rows, n_slices;
+    partition_sizes(p, &n_imp, &n_tbm);
+    const bool split = ems::decode_split(p->budget, n_imp, n_tbm, p->window, p->dtype == EMS_F32, &slice_rows, &n_slices);
+    const size_t bkv = (size_t)p->batch * p->kv_heads;
+    return decode_stage_bytes(p) + (split ? align_up(sizeof(float) * bkv * ems::kDecodeHandFloats) : 0);
 }
 
 static bool state_ok(const ems_decode_state* s)
@@ -535,6 +546,8 @@ int ems_decode_step(const ems_params* p, const ems_decode_state* state, int32_t 
     a.q_new = q_new; a.k_new = k_new; a.v_new = v_new;
     a.attn_opt = attn_opt; a.decision_opt = decision_opt; a.sim_opt = sim_opt;
     a.ws = static_cast<float*>(ws);
+    if (ems::decode_split(p->budget, n_imp, n_tbm, p->window, p->dtype == EMS_F32, &a.slice_rows, &a.n_slices))
+        a.hand = reinterpret_cast<float*>(static_cast<char*>(ws) + decode_stage_bytes(p));
     // per-row dot products and row norms are staged in LDS when they fit in
     // what a block may ask for without raising the limit, else in the workspace
     const size_t stage_floats = (size_t)(g + 1) * p->budget;

@@ -118,6 +118,8 @@ struct DecodeStepArgs {
     int32_t* decision_opt;  // [bkv, 2] or null
     float* sim_opt;         // [bkv] or null
     float* ws;              // [bkv, (group + 1) * budget] staging when it does not fit in LDS
+    float* hand;            // [bkv, kDecodeHandFloats] hand-over record of the sliced step, else null
+    int slice_rows, n_slices;   // row slices of the sliced step (decode_split); 0, 1 = one launch
     int lds_floats;         // (group + 1) * budget when staged in LDS, else 0
     int bkv, group, head_dim, seq_len, window, budget, n_imp, n_tbm;
     int step;               // >= 0, or -1: read st.step_count
@@ -144,6 +146,9 @@ hipError_t launch_sparsity(const StatsArgs& a, hipStream_t st);
 hipError_t launch_redundancy(const StatsArgs& a, bool f32, hipStream_t st);
 hipError_t launch_decode_init(const DecodeInitArgs& a, bool f32, hipStream_t st);
 hipError_t launch_decode_step(const DecodeStepArgs& a, bool f32, hipStream_t st);
+constexpr int kDecodeMaxSlices = 32;     // row slices per head of the sliced decode step
+constexpr int kDecodeHandFloats = 384;   // floats of its per-head hand-over record
+bool decode_split(int budget, int n_imp, int n_tbm, int window, bool f32, int* slice_rows, int* n_slices);
 hipError_t launch_expand(const ExpandArgs& a, bool f32, hipStream_t st);
 hipError_t launch_score_pass1(const ScoreArgs& a, bool f32, hipStream_t st);   // rows' log-sum-exp
 hipError_t launch_score_pass2(const ScoreArgs& a, bool f32, hipStream_t st);   // column sums

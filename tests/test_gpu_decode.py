@@ -134,12 +134,15 @@ def test_decode_init_matches_oracle(shape, mode):
 
 
 # a budget whose per-row staging does not fit in LDS: the kernel stages in the workspace instead
+# large caches: in bf16 the step runs as four launches over row slices; BIG stages its row dots in the
+# workspace (they do not fit in LDS), BIG_LDS in LDS
 BIG = (1, 8, 1, 64, 4000, 8, 1800, 0.5)
+BIG_LDS = (1, 8, 2, 128, 5000, 16, 1100, 0.5)
 
 
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("tau", [0.3, -2.0, 2.0])
-@pytest.mark.parametrize("shape", SHAPES + [BIG])
+@pytest.mark.parametrize("shape", SHAPES + [BIG, BIG_LDS])
 def test_decode_steps_match_oracle(shape, tau, mode):
     _log("decode_step", shape, "tau", tau, "mode", mode)
     p, merged, tbm, s_glo, s_loc, st = _prefill(shape, mode, tau, seed=shape[6])
@@ -162,7 +165,7 @@ def test_decode_steps_match_oracle(shape, tau, mode):
         assert n_merge == 0
     elif tau <= -1:
         assert n_evict == 0
-    elif shape != BIG:                                    # with 1792 random centres something is always similar
+    elif shape not in (BIG, BIG_LDS):                     # with a thousand random centres something is always similar
         assert n_merge > 0 and n_evict > 0, (n_merge, n_evict)
 
 
