@@ -97,8 +97,13 @@ SELECT_SHAPES = [
     (2, 4099, 32, 256, 0.5, 7),
     (2, 3000, 64, 128, 3.0, 1),
     (1, 200, 10, 190, 5.0, 3),       # N_tbm clamped, everything kept or merged
-    (1, 70000, 64, 2048, 0.5, 7),    # more than 64 elements per thread
+    (1, 70000, 64, 2048, 0.5, 7),    # long sequences: chunks of 2048 positions over many blocks per head
     (2, 33, 1, 2, 0.0, 1),
+    (3, 8192, 32, 100, 0.5, 7),      # the longest sequence the one-block kernel takes
+    (3, 8193, 32, 100, 0.5, 7),      # the shortest the chunked kernels take: a second chunk of one position
+    (2, 20000, 2047, 4000, 1.0, 5),  # window ends inside a chunk; a large budget (many candidates)
+    (1, 12288, 4096, 8000, 0.5, 63), # whole chunks inside the window; widest pooling kernel
+    (2, 10000, 8, 9000, 0.5, 1),     # nearly everything kept: the candidate list is almost the whole head
 ]
 
 
@@ -131,12 +136,16 @@ def test_select_matches_oracle(shape):
         assert is_sorted_unique(imp[0, h]) and (tbm.shape[-1] == 0 or is_sorted_unique(tbm[0, h]))
 
 
-def test_select_exact_ties_rank_by_position():
-    """Scores quantised to a few levels: almost everything ties; pooling off so the keys are
-    exactly the inputs and the index sets must equal the oracle's exactly."""
-    bh, n, w, nb = 2, 5000, 16, 300
+@pytest.mark.parametrize("levels", [4, 1])
+@pytest.mark.parametrize("n", [5000, 20000])
+def test_select_exact_ties_rank_by_position(n, levels):
+    """Scores quantised to a few levels (or all equal): almost everything ties, on the chunked path the
+    candidate list is then most of the head; pooling off so the keys are exactly the inputs and the
+    index sets must equal the oracle's exactly."""
+    bh, w, nb = 2, 16, 300
+    _log("select ties", n, levels)
     rng = np.random.default_rng(1)
-    loc = rng.integers(1, 5, (1, bh, n)).astype(np.float32)
+    loc = rng.integers(1, levels + 1, (1, bh, n)).astype(np.float32)
     glo = np.full((1, bh, n), 1e-6, np.float32)      # aligned s_glo never wins the max
     p = B.EmsParams(1, bh, bh, 64, n, w, nb, merge_ratio=2.0, pool_kernel=1)
     imp, tbm = B.ems_select(p, torch.from_numpy(glo).cuda(), torch.from_numpy(loc).cuda())
