@@ -77,7 +77,7 @@ __device__ __forceinline__ void hist_add(int* hist, int digit, bool on)
 // the whole chip works on the O(N) part; the exact ranking is then done by one block per head
 // on a short list of candidates.  Four launches, in stream order:
 //   A  select_sums_kernel     per-chunk sums of s_glo and s_loc (fixed-order trees)
-//   B  select_keys_kernel     Eq. 2 with the head's factor (chunk sums added in chunk order),
+//   B  select_keys_kernel     Eq. 2 with the head's factor (chunk sums added in a fixed tree),
 //                             mean pooling, ranking keys written, and a histogram of the keys'
 //                             12 leading bits per head (integer atomics: order-free)
 //   C  select_gather_kernel   the leading-bit bin that holds the last rank wanted (N_imp +
@@ -140,21 +140,24 @@ __global__ __launch_bounds__(kChunkBlock) void select_keys_kernel(SelectArgs a)
         g[i] = j < N ? glo[j] : 0.f;
         l[i] = j < N ? loc[j] : 0.f;
     }
-    // Eq. 2 factor: the chunk sums are fetched by as many threads at once and added in chunk order
-    __shared__ float sums_sm[2 * kChunkBlock];
+    // Eq. 2 factor: thread t adds the sums of chunks t, t + 256, ..., the wave adds its lanes with a
+    // fixed butterfly, thread 0 adds the four waves in order -- the same tree in every block of the
+    // head, so they all get the same factor bit for bit
+    __shared__ float sums_sm[kChunkBlock / kWave][2];
     float tg = 0.f, tl = 0.f;
-    for (int c0s = 0; c0s < (int)gridDim.x; c0s += kChunkBlock) {
-        const int c = c0s + tid;
-        if (c < (int)gridDim.x) {
-            sums_sm[2 * tid] = a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 0];
-            sums_sm[2 * tid + 1] = a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 1];
-        }
-        __syncthreads();
-        if (tid == 0)
-            for (int c = 0; c < min(kChunkBlock, (int)gridDim.x - c0s); ++c) { tg += sums_sm[2 * c]; tl += sums_sm[2 * c + 1]; }
-        __syncthreads();
+    for (int c = tid; c < (int)gridDim.x; c += kChunkBlock) {
+        tg += a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 0];
+        tl += a.chunk_sums[((size_t)head * gridDim.x + c) * 2 + 1];
     }
-    if (tid == 0) align_sm = (tl / (float)N) / (tg / (float)N);
+    tg = wave_sum(tg); tl = wave_sum(tl);
+    if (tid % kWave == 0) { sums_sm[tid / kWave][0] = tg; sums_sm[tid / kWave][1] = tl; }
+    __syncthreads();
+    if (tid == 0) {
+        float sg = 0.f, sl = 0.f;
+#pragma unroll
+        for (int w = 0; w < kChunkBlock / kWave; ++w) { sg += sums_sm[w][0]; sl += sums_sm[w][1]; }
+        align_sm = (sl / (float)N) / (sg / (float)N);
+    }
     __syncthreads();
     const float align = align_sm;
     const int half = (a.pool_kernel - 1) / 2;
@@ -173,12 +176,19 @@ __global__ __launch_bounds__(kChunkBlock) void select_keys_kernel(SelectArgs a)
     const float div = (float)a.pool_kernel;
     float* pooled = a.pooled + (size_t)head * N;
     float* s_out = a.s_gl_opt ? a.s_gl_opt + (size_t)head * N : nullptr;
+    // the window runs in the outer loop so that each step issues the thread's eight independent LDS
+    // reads together (every element still adds its neighbours from left to right)
+    float acc[kPerThread];
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) acc[i] = 0.f;
+    for (int t = 0; t <= 2 * half; ++t) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) acc[i] += comb_sm[i * kChunkBlock + tid + t];
+    }
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
-        const int r = i * kChunkBlock + tid, j = c0 + r;
-        float acc = 0.f;
-        for (int t = 0; t <= 2 * half; ++t) acc += comb_sm[r + t];
-        const float v = acc / div;
+        const int j = c0 + i * kChunkBlock + tid;
+        const float v = acc[i] / div;
         if (j < N) { pooled[j] = v; if (s_out) s_out[j] = v; }
         hist_add(hist, (int)(order_key(v) >> (32 - kCoarseBits)), j < Nc);
     }
