@@ -141,3 +141,23 @@ def test_redundancy_at_is_the_same_loop_on_chosen_tokens():
     np.testing.assert_array_equal(ems_ref.redundancy_at(_p(n, h=h, d=d), k, v, tokens), best[..., tokens])
     with pytest.raises(ValueError):
         ems_ref.redundancy_at(_p(n, h=h, d=d), k, v, np.array([70], np.int32))
+
+
+def test_redundancy_at_against_dense_cosine_products():
+    """The sampled form on its own against Eq. 4 written out with numpy: for a chosen token t the best
+    product of key and value cosines over the strictly earlier tokens (none for t = 0)."""
+    n, h, d = 90, 2, 32
+    inp = ems_inputs.small(1, h, h, d, n, seed=8)
+    k, v = inp.f32("k").copy(), inp.f32("v").copy()
+    k[0, :, 61], v[0, :, 61] = 3.0 * k[0, :, 12], 0.25 * v[0, :, 12]     # a scaled copy of an earlier token
+    tokens = np.array([0, 1, 2, 40, 61, 89], np.int32)
+    got = ems_ref.redundancy_at(_p(n, h=h, d=d), k, v, tokens)
+    for i in range(h):
+        uk, uv = _unit(k[0, i]), _unit(v[0, i])
+        for c, t in enumerate(tokens):
+            if t == 0:
+                assert got[0, i, c] == -np.inf
+                continue
+            want = ((uk[:t] @ uk[t]) * (uv[:t] @ uv[t])).max()
+            np.testing.assert_allclose(got[0, i, c], want, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(got[0, :, 4], 1.0, rtol=1e-12)
