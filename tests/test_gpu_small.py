@@ -104,6 +104,8 @@ SELECT_SHAPES = [
     (2, 20000, 2047, 4000, 1.0, 5),  # window ends inside a chunk; a large budget (many candidates)
     (1, 12288, 4096, 8000, 0.5, 63), # whole chunks inside the window; widest pooling kernel
     (2, 10000, 8, 9000, 0.5, 1),     # nearly everything kept: the candidate list is almost the whole head
+    (1, 1000003, 64, 3000, 0.5, 7),  # 489 chunks: more than one chunk per thread when the factor is formed
+    (1, 1 << 22, 64, 5000, 1.0, 7),  # the longest sequence the interface takes: 2048 chunks
 ]
 
 
