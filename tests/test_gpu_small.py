@@ -242,6 +242,12 @@ def test_evict_merge_matches_oracle(shape, tau, mode):
         assert (out["tbm_dest"] < n_imp).any() and (out["tbm_dest"] == nb).any()
 
 
+def test_evict_merge_many_centres():
+    """12000 class centres (the destination search cuts them into 16 slices of three rounds each) and 6016
+    to-be-merged tokens (two LDS pieces in the merge), checked like the small shapes."""
+    test_evict_merge_matches_oracle((1, 1, 128, 40000, 32, 12032, 0.5), 0.22, B.EMS_BF16)
+
+
 def test_merge_ratio_zero_is_bit_exact_gather():
     b, hkv, d, n, w, nb = 1, 2, 128, 900, 32, 100
     inp = ems_inputs.small(b, hkv, hkv, d, n, seed=4)
