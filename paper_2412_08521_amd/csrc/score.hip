@@ -98,6 +98,14 @@ __device__ __forceinline__ void wait_vmem_all_visible()
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt left alone
 }
 
+// One wait for every LDS read in flight, in the form the compiler can see.  Placed well after a
+// batch of fragment reads, it replaces the separate wait the compiler would otherwise put in
+// front of each fragment's first use (a dozen scalar instructions per stage).
+__device__ __forceinline__ void wait_lds_all_visible()
+{
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), vmcnt and expcnt left alone
+}
+
 // The hardware deals workgroups to the 8 XCDs (each with its own L2) round-robin in launch
 // order.  Work is cut into groups of `per_group` consecutive work items that stream the
 // same operand; group g is given to XCD g % 8 so that the group shares one L2.  Returns
@@ -462,14 +470,38 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         frag_t aq[2][kFrags];
         f32x16_t lse_v[2];
         f32x16_t acc[4];
-        // issue cursor: ring slot, q-head and first row of the next stage to fetch
+        // issue cursor of the next stage to fetch.  Where four DMA instructions go under one M0, the
+        // cursor is kept as running addresses (source rows, their log-sum-exp, the two ring slots)
+        // that advance by constants: a stage, or at the last stage of a q-head the jump to the next
+        // head's first interior row -- a handful of scalar instructions per stage.
+        constexpr bool kRunning = kKeepDmaOff && kQInstr % 4 == 0;
         int u_next = 0, slot_next = 0, g_next = 0, row_next = e_end;
+        const char* q_src = reinterpret_cast<const char*>(Q0) + (size_t)e_end * kRowBytes;
+        const float* l_src = L0 + e_end;
+        unsigned dst_q = lds_q0, dst_l = lds_l0;
+        const long long q_jump = ((long long)N - (i_end - e_end) + kStreamRows) * kRowBytes;   // last stage of a head -> next head
+        const long long l_jump = (long long)a.n_pad - (i_end - e_end) + kStreamRows;
+        const unsigned lse_lane_off = (unsigned)col * 4u;
         auto issue_next = [&]() __attribute__((always_inline)) {
-            issue(g_next, row_next, slot_next, std::true_type{});
+            if constexpr (kRunning) {
+#pragma unroll
+                for (int j = 0; j < kQInstr; j += 4)
+                    dma_to_lds_x4(q_src + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst_q + j * 1024);
+                dma_to_lds<4>(l_src, lse_lane_off, dst_l);
+            } else {
+                issue(g_next, row_next, slot_next, std::true_type{});
+            }
             ++u_next;
-            slot_next = slot_next + 1 == kRing ? 0 : slot_next + 1;
             const bool more = u_next < n_stages;            // else: stay on the last stage
             const bool wrap = row_next + kStreamRows >= i_end;
+            const bool ring_wrap = slot_next + 1 == kRing;
+            slot_next = ring_wrap ? 0 : slot_next + 1;
+            if constexpr (kRunning) {
+                dst_q = ring_wrap ? lds_q0 : dst_q + kStageBytes;
+                dst_l = ring_wrap ? lds_l0 : dst_l + 2 * kStreamRows * 4;
+                q_src += more ? (wrap ? q_jump : (long long)kStreamRows * kRowBytes) : 0ll;
+                l_src += more ? (wrap ? l_jump : (long long)kStreamRows) : 0ll;
+            }
             const int row_adv = wrap ? e_end : row_next + kStreamRows;
             g_next = more && wrap ? g_next + 1 : g_next;
             row_next = more ? row_adv : row_next;
@@ -494,7 +526,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         // instructions after the chain that wrote it has ended.
         auto stage = [&](int t, auto set_c) __attribute__((always_inline)) {
             constexpr int set = decltype(set_c)::value;
-            constexpr int kFetchAt = kPairs - 1;            // late: the DMA has had most of a stage more to land
+            constexpr int kFetchAt = 1;                     // as early as the other register set is free: the LDS latency has three rounds to hide in
             issue_next();                                   // stage t + kRing - 1
 #pragma unroll
             for (int p = 0; p < kPairs; ++p) {
@@ -530,6 +562,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                         wait_vmem<(kRing - 2) * kLoads>();
                         fetch_rows((t + 1) % kRing, aq[1 - set], lse_v[1 - set]);
                     }
+                    // two rounds later those reads have long returned: one wait for all of them
+                    if (kPairs > 2 && kFetchAt < kPairs - 1 && p == kPairs - 1 && f == 0) wait_lds_all_visible();
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -811,10 +845,12 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 #pragma unroll
                     for (int e = 0; e < kEps; ++e)
                         lsum[psa + 1][e] += exp2_fast(__builtin_fmaf(prevB[f * kEps + e], c, -m_fix[psa + 1]));
-                    if (kPairs > 1 && p == kPairs - 1 && f == 0) {   // the other register set is free
+                    if (kPairs > 1 && p == 1 && f == 0) {   // the other register set is free; early, so that the LDS latency hides
                         wait_vmem<(kRing - 2) * kLoads>();
                         fetch_keys((u + 1) % kRing, ak[1 - set]);
                     }
+                    // two rounds later those reads have long returned: one wait for all of them
+                    if (kPairs > 2 && p == kPairs - 1 && f == 0) wait_lds_all_visible();
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
