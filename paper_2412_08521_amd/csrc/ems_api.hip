@@ -78,7 +78,7 @@ void partition_sizes(const ems_params* p, int* n_imp, int* n_tbm)
 
 struct ScorePlan {
     int n_chunks, chunk_rows, loc_chunk0, n_pad, p1_splits;
-    size_t off_lse2, off_part_glo, off_part_loc, off_part_m, off_part_l, total;
+    size_t off_lse2, off_part_glo, off_part_loc, off_part_m, off_part_l, off_queue, total;
 };
 
 // Row chunks of the key-stationary pass: small enough that there are tens of thousands of
@@ -125,6 +125,7 @@ ScorePlan plan_score(const ems_params* p)
         const size_t one = align_up(sizeof(float) * (size_t)s.p1_splits * p->batch * p->q_heads * s.n_pad);
         off += one; s.off_part_l = off; off += one;
     }
+    s.off_queue = off; off += kAlign;                                   // work-queue cursors of the second pass
     s.total = off;
     return s;
 }
@@ -229,6 +230,7 @@ static void fill_score_args(ems::ScoreArgs& a, const ems_params* p, const ScoreP
     a.part_loc = w ? reinterpret_cast<float*>(w + plan.off_part_loc) : nullptr;
     a.part_m = w ? reinterpret_cast<float*>(w + plan.off_part_m) : nullptr;
     a.part_l = w ? reinterpret_cast<float*>(w + plan.off_part_l) : nullptr;
+    a.queue = w ? reinterpret_cast<int*>(w + plan.off_queue) : nullptr;
     a.p1_splits = plan.p1_splits;
     a.batch = p->batch; a.q_heads = p->q_heads; a.kv_heads = p->kv_heads;
     a.head_dim = p->head_dim; a.seq_len = p->seq_len; a.window = p->window;
@@ -254,6 +256,7 @@ int ems_global_local_score(const ems_params* p, const void* q, const void* k,
     fill_score_args(a, p, plan, ws);
     const hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e = ems::launch_score_pass1(a, p->dtype == EMS_F32, st);
+    a.queue_clear = 1;                                      // the first pass cleared the second pass's cursors
     if (e == hipSuccess) e = ems::launch_score_pass2(a, p->dtype == EMS_F32, st);
     return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
 }

@@ -122,6 +122,53 @@ static unsigned xcd_grid(int n_groups, int per_group)
     return (unsigned)(kXcds * ((n_groups + kXcds - 1) / kXcds) * per_group);
 }
 
+// ---- work queues (second pass).  The XCDs of one chip do not run at the same speed (a few percent apart under
+// this load), and the hardware deals workgroups to them in fixed turns, so a launch whose work is
+// bound to block indices ends when the slowest XCD ends.  Instead a wave takes its work item at
+// run time: from the queue of its XCD (items that stream the same operand stay on one L2) and,
+// once that is empty, from a pool of the lightest items that every XCD draws from.  One integer
+// atomic per item; which wave computes an item has no influence on the item's result.  Returns
+// the item's index in its queue (pool = true: in the pool), or -1 when both are empty.
+__device__ __forceinline__ int take_work_item(int* cursors, int n_local, int n_pool, bool dynamic, bool& pool)
+{
+    if (!dynamic) {
+        // short launches: one item per block, fixed by the block index (block b is the (b / 8)-th
+        // of its XCD: first the XCD's queue, then every eighth item of the pool)
+        const int x = blockIdx.x % kXcds, i = blockIdx.x / kXcds;
+        pool = i >= n_local;
+        const int k = pool ? (i - n_local) * kXcds + x : i;
+        return pool && k >= n_pool ? -1 : k;
+    }
+    int k = -1, from_pool = 0;
+    if (threadIdx.x == 0) {
+        if (n_local > 0) {
+            k = atomicAdd(&cursors[blockIdx.x % kXcds], 1);
+            if (k >= n_local) k = -1;
+        }
+        if (k < 0 && n_pool > 0) {
+            k = atomicAdd(&cursors[kXcds], 1);
+            from_pool = 1;
+            if (k >= n_pool) k = -1;
+        }
+    }
+    pool = __builtin_amdgcn_readfirstlane(from_pool) != 0;
+    return __builtin_amdgcn_readfirstlane(k);
+}
+
+__global__ void score_queue_reset_kernel(int* queue)
+{
+    if (threadIdx.x < kXcds + 1) queue[threadIdx.x] = 0;
+}
+
+// Pass 2: key tiles at or below the diagonal of row chunks 0..I, per (batch, kv-head): chunk I'
+// has min(n_key_tiles, (I' + 1) * r) of them, r = chunk rows / keys per tile.
+__host__ __device__ inline long long p2_items_upto(int I, int r, int n_key_tiles)
+{
+    const long long n = I + 1;
+    const long long whole = n < n_key_tiles / r ? n : n_key_tiles / r;    // chunks whose count is not capped
+    return r * whole * (whole + 1) / 2 + (n - whole) * n_key_tiles;
+}
+
 // sum of the 16 accumulator-derived values with four independent partial sums
 __device__ __forceinline__ float sum16(const float (&p)[16])
 {
@@ -216,6 +263,7 @@ __global__ __launch_bounds__(256) void lse_to_base2_kernel(ScoreArgs a)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int bh = blockIdx.y;
+    if (blockIdx.x == 0 && bh == 0 && threadIdx.x < kXcds + 1) a.queue[threadIdx.x] = 0;   // the pass that follows starts on empty queues
     if (i >= a.n_pad) return;
     a.lse2[(size_t)bh * a.n_pad + i] =
         i < a.seq_len ? a.lse_in_nat[(size_t)bh * a.seq_len + i] * 1.44269504088896340736f : INFINITY;
@@ -301,16 +349,36 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int n_key_tiles = (N + kKeys - 1) / kKeys;
     const int n_chunks = a.n_chunks, R = a.chunk_rows;
 
-    int bid = xcd_work_item(a.batch * a.kv_heads * n_chunks, n_key_tiles);
-    if (bid < 0) return;
-    const int J = bid % n_key_tiles; bid /= n_key_tiles;
+    // Work item = (row chunk I, (batch, kv-head), key tile J at or below the chunk's diagonal),
+    // heaviest chunks first.  An XCD's queue holds the chunks from the top down to p2_split for
+    // its share of the heads (head = XCD + 8 m), key tiles innermost, so that the waves of an XCD
+    // stream the same query rows; the chunks below p2_split, all heads, are the pool.
     const int BKV = a.batch * a.kv_heads;
-    const int bkv = bid % BKV;
-    const int I = n_chunks - 1 - bid / BKV;                 // heaviest row chunks first
+    // Long launches: a wave stays and takes item after item until the queues are empty -- the exit
+    // every wave reaches (the cursors only grow); between two items nothing of the wave is in flight.
+    // Short launches: one item per block.
+    for (bool first = true; first || a.q_dynamic; first = false) {
+    bool pool;
+    const int k = take_work_item(a.queue, a.p2_local, a.p2_pool, a.q_dynamic != 0, pool);
+    if (k < 0) break;
+    const int r_tiles = R / kKeys;
+    const int top = pool ? a.p2_split - 1 : n_chunks - 1;
+    const long long per = pool ? BKV : a.q_share;           // heads per chunk in this queue
+    const long long upto_top = p2_items_upto(top, r_tiles, n_key_tiles);
+    int lo = pool ? 0 : a.p2_split, hi = top;               // the chunk whose items include k: the smallest I with before(I) <= k
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (per * (upto_top - p2_items_upto(mid, r_tiles, n_key_tiles)) <= k) hi = mid; else lo = mid + 1;
+    }
+    const int I = lo;
+    const int rem = (int)(k - per * (upto_top - p2_items_upto(I, r_tiles, n_key_tiles)));
+    const int cnt = min(n_key_tiles, (I + 1) * r_tiles);
+    const int J = rem % cnt;
+    const int bkv = pool ? rem / cnt : (int)(blockIdx.x % kXcds) + kXcds * (rem / cnt);
     const int key_base = J * kKeys;
     const int r_begin = max(I * R, key_base);               // both multiples of 32
     const int r_end = min((I + 1) * R, N);
-    if (r_begin >= r_end) return;                           // pair above the diagonal
+    if (r_begin >= r_end) continue;                         // (the queues hold no pair above the diagonal)
     // [r_begin, e_end) touches the diagonal, [e_end, i_end) is interior, [i_end, r_end) holds
     // window rows (each range may be empty; all bounds but r_end are multiples of 32)
     const int win0 = N - W;
@@ -351,11 +419,10 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         const int slot = j * kWave + ln, row = slot / kCpr;
         return (unsigned)row * kRowBytes + (unsigned)(((slot % kCpr) ^ swz_key<T, D>(row)) << 4);
     };
-    unsigned dma_off[kKeepDmaOff ? kQInstr : 1];
     unsigned dma_rel[kKeepDmaOff ? kQInstr : 1];            // the same, relative to the start of the instruction's 1 KiB
     if (kKeepDmaOff) {
 #pragma unroll
-        for (int j = 0; j < kQInstr; ++j) { dma_off[j] = dma_src_off(j, lane); dma_rel[j] = dma_off[j] - (unsigned)j * 1024u; }
+        for (int j = 0; j < kQInstr; ++j) dma_rel[j] = dma_src_off(j, lane) - (unsigned)j * 1024u;
     }
     unsigned frag_off[kFrags];
 #pragma unroll
@@ -381,14 +448,14 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             } else {
 #pragma unroll
                 for (int j = 0; j < kQInstr; ++j)
-                    dma_to_lds<16>(base, kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln), dst + j * 1024);
+                    dma_to_lds<16>(base, kKeepDmaOff ? dma_rel[j] + (unsigned)j * 1024u : dma_src_off(j, ln), dst + j * 1024);
             }
         } else {                                            // rows past the end re-read the last row
 #pragma unroll
             for (int j = 0; j < kQInstr; ++j) {
                 const int r = (j * kWave + lane) / kCpr;
                 const int over = max(row + r - (N - 1), 0);
-                const unsigned off = kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln);
+                const unsigned off = kKeepDmaOff ? dma_rel[j] + (unsigned)j * 1024u : dma_src_off(j, ln);
                 dma_to_lds<16>(qg, (unsigned)row * kRowBytes + off - (unsigned)over * kRowBytes, dst + j * 1024);
             }
         }
@@ -608,6 +675,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             if (out_loc) out_loc[kj] = lsum;
         }
     }
+    }   // next work item
 }
 
 // ------------------------------------------------------------------------------------
@@ -649,6 +717,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int N = a.seq_len;
     const int n_row_tiles = (N + kRows - 1) / kRows;
     const int G = a.q_heads / a.kv_heads;
+    // the second pass takes its work from queues whose cursors start at zero; it runs after this
+    // kernel has ended, so its first block clears them
+    if (blockIdx.x == 0 && threadIdx.x < kXcds + 1) a.queue[threadIdx.x] = 0;
     int bid = xcd_work_item(a.p1_groups, a.p1_per_group);
     if (bid < 0) return;
     const int S = a.p1_splits, sp = bid % S; bid /= S;           // this wave's share of the key range
@@ -959,8 +1030,30 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
         hipLaunchKernelGGL(lse_to_base2_kernel, g, dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     }
-    const unsigned grid2 = xcd_grid(BKV * a.n_chunks, n_key_tiles);
-    hipLaunchKernelGGL((score_pass2_stream_kernel<T, D>), dim3(grid2), dim3(kWave), 0, st, a);
+    // Queues: an XCD queue per share of the heads when they divide over the XCDs, else one pool
+    // for everything.  With at least four rounds of items per resident wave (one wave per SIMD:
+    // 128 per XCD) the waves stay and draw from the cursors, and the lightest row chunks -- about
+    // 4.5 % of the items, which covers the spread between XCDs; more costs more in lost L2 sharing
+    // than it balances -- go to the pool; shorter launches get one block per item.
+    ScoreArgs a2 = a;
+    const int r_tiles = a.chunk_rows / kKeys, top = a.n_chunks - 1;
+    const long long all = p2_items_upto(top, r_tiles, n_key_tiles);
+    a2.q_share = BKV % kXcds == 0 ? BKV / kXcds : 0;
+    a2.q_dynamic = (long long)BKV * all >= 4ll * 128 * kXcds;
+    a2.p2_split = a2.q_share ? 0 : a.n_chunks;
+    if (a2.q_share && a2.q_dynamic)
+        while (a2.p2_split < top && p2_items_upto(a2.p2_split, r_tiles, n_key_tiles) <= all * 45 / 1000) ++a2.p2_split;
+    const long long low = p2_items_upto(a2.p2_split - 1, r_tiles, n_key_tiles);
+    const long long n_local = a2.q_share * (all - low), n_pool = (long long)BKV * low;
+    const long long per_xcd = n_local + (n_pool + kXcds - 1) / kXcds;
+    const long long grid2 = kXcds * (a2.q_dynamic ? 128 : per_xcd);
+    if (a.chunk_rows % kKeys != 0 || grid2 > 0x7fffffffll) return hipErrorInvalidValue;
+    a2.p2_local = (int)n_local; a2.p2_pool = (int)n_pool;
+    if (a2.q_dynamic && !a.lse_in_nat && !a.queue_clear) {  // (the conversion kernel above, or the first pass's launch, cleared them already)
+        hipLaunchKernelGGL(score_queue_reset_kernel, dim3(1), dim3(64), 0, st, a.queue);
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    }
+    hipLaunchKernelGGL((score_pass2_stream_kernel<T, D>), dim3((unsigned)grid2), dim3(kWave), 0, st, a2);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
