@@ -26,9 +26,12 @@ struct ScoreArgs {
     int p1_splits;      // pass 1: key-range splits per row tile (1 = none)
     float* part_m;      // [p1_splits, B*Hq, n_pad] partial running maxima (workspace, p1_splits > 1)
     float* part_l;      // [p1_splits, B*Hq, n_pad] partial sums relative to them
-    // Work queues of the second pass (set by the launcher): a wave takes its work items from the queue
-    // of its XCD and, once that is empty, from a pool every XCD draws from.
-    int* queue;         // [kXcds + 1] cursors (workspace; cleared before the pass)
+    // Work queues (set by the launchers): a wave takes its work items from the queue of its XCD; once
+    // that is empty, the first pass goes on with another XCD's queue, the second pass with a pool that
+    // every XCD draws from.
+    int* queue;         // [2][kXcds + 1] cursors: second pass, first pass (workspace; cleared before a pass)
+    int p1_local;       // first pass: items per XCD queue
+    int p1_dynamic;     // first pass: 1 = waves stay and draw (and steal), 0 = one item per block
     int queue_clear;    // the cursors are known to be clear (the pass follows the first pass's launch)
     int q_dynamic;      // 1: waves stay and take items from the cursors; 0: one item per block, by block index
     int q_share;        // (batch * kv_heads) / 8 heads per XCD queue; 0 = everything is in the pool

@@ -107,27 +107,29 @@ __device__ __forceinline__ void wait_lds_all_visible()
 }
 
 // The hardware deals workgroups to the 8 XCDs (each with its own L2) round-robin in launch
-// order.  Work is cut into groups of `per_group` consecutive work items that stream the
-// same operand; group g is given to XCD g % 8 so that the group shares one L2.  Returns
-// the linear work-item index, or -1 for a padding block.
+// order: block b runs on XCD b % 8.  First pass: work is cut into groups of `per_group`
+// consecutive work items that stream the same operand; group g belongs to XCD g % 8 so that the
+// group shares one L2.  Returns the linear index of the k-th work item of XCD `xcd`, or -1 for
+// padding.
 constexpr int kXcds = 8;
-__device__ __forceinline__ int xcd_work_item(int n_groups, int per_group)
+__device__ __forceinline__ int xcd_work_item(int n_groups, int per_group, int xcd, int k)
 {
-    const int xcd = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
     const int group = (k / per_group) * kXcds + xcd;
     return group < n_groups ? group * per_group + k % per_group : -1;
 }
-static unsigned xcd_grid(int n_groups, int per_group)
+static unsigned xcd_grid(int n_groups, int per_group)    // 8 x (items per XCD, padding included)
 {
     return (unsigned)(kXcds * ((n_groups + kXcds - 1) / kXcds) * per_group);
 }
 
-// ---- work queues (second pass).  The XCDs of one chip do not run at the same speed (a few percent apart under
+// ---- work queues.  The XCDs of one chip do not run at the same speed (a few percent apart under
 // this load), and the hardware deals workgroups to them in fixed turns, so a launch whose work is
-// bound to block indices ends when the slowest XCD ends.  Instead a wave takes its work item at
-// run time: from the queue of its XCD (items that stream the same operand stay on one L2) and,
-// once that is empty, from a pool of the lightest items that every XCD draws from.  One integer
-// atomic per item; which wave computes an item has no influence on the item's result.  Returns
+// bound to block indices ends when the slowest XCD ends, with the re-dispatch of a workgroup per
+// item on top.  In long launches a wave therefore stays resident and takes its work items at run
+// time, one integer atomic per item; which wave computes an item has no influence on the item's
+// result.
+// Second pass: from the queue of its XCD (items that stream the same operand stay on one L2)
+// and, once that is empty, from a pool of the lightest items that every XCD draws from.  Returns
 // the item's index in its queue (pool = true: in the pool), or -1 when both are empty.
 __device__ __forceinline__ int take_work_item(int* cursors, int n_local, int n_pool, bool dynamic, bool& pool)
 {
@@ -155,9 +157,28 @@ __device__ __forceinline__ int take_work_item(int* cursors, int n_local, int n_p
     return __builtin_amdgcn_readfirstlane(k);
 }
 
+// First pass: every XCD has a queue (its items in the fixed order of xcd_work_item, padding
+// included); a wave whose own queue is empty goes on with the next item of another XCD's queue,
+// so the faster XCDs help the slower ones finish.  Returns the item's index in the queue of XCD
+// `from`, or -1 when every queue is empty.
+__device__ __forceinline__ int take_or_steal(int* cursors, int n_per_queue, int& from)
+{
+    int k = -1, q = 0;
+    if (threadIdx.x == 0) {
+        const int own = blockIdx.x % kXcds;
+        for (int d = 0; d < kXcds && k < 0; ++d) {
+            q = (own + d) % kXcds;
+            k = atomicAdd(&cursors[q], 1);
+            if (k >= n_per_queue) k = -1;
+        }
+    }
+    from = __builtin_amdgcn_readfirstlane(q);
+    return __builtin_amdgcn_readfirstlane(k);
+}
+
 __global__ void score_queue_reset_kernel(int* queue)
 {
-    if (threadIdx.x < kXcds + 1) queue[threadIdx.x] = 0;
+    if (threadIdx.x < 2 * (kXcds + 1)) queue[threadIdx.x] = 0;      // both passes' cursors
 }
 
 // Pass 2: key tiles at or below the diagonal of row chunks 0..I, per (batch, kv-head): chunk I'
@@ -263,7 +284,7 @@ __global__ __launch_bounds__(256) void lse_to_base2_kernel(ScoreArgs a)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int bh = blockIdx.y;
-    if (blockIdx.x == 0 && bh == 0 && threadIdx.x < kXcds + 1) a.queue[threadIdx.x] = 0;   // the pass that follows starts on empty queues
+    if (blockIdx.x == 0 && bh == 0 && threadIdx.x < 2 * (kXcds + 1)) a.queue[threadIdx.x] = 0;   // the pass that follows starts on empty queues
     if (i >= a.n_pad) return;
     a.lse2[(size_t)bh * a.n_pad + i] =
         i < a.seq_len ? a.lse_in_nat[(size_t)bh * a.seq_len + i] * 1.44269504088896340736f : INFINITY;
@@ -717,11 +738,15 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int N = a.seq_len;
     const int n_row_tiles = (N + kRows - 1) / kRows;
     const int G = a.q_heads / a.kv_heads;
-    // the second pass takes its work from queues whose cursors start at zero; it runs after this
-    // kernel has ended, so its first block clears them
-    if (blockIdx.x == 0 && threadIdx.x < kXcds + 1) a.queue[threadIdx.x] = 0;
-    int bid = xcd_work_item(a.p1_groups, a.p1_per_group);
-    if (bid < 0) return;
+    // A wave stays and takes item after item until every queue is empty: the exit every wave
+    // reaches (the cursors only grow); between two items nothing of the wave is in flight.
+    // (Short launches: one item per block, by block index.)
+    for (bool first = true; first || a.p1_dynamic; first = false) {
+    int from_xcd = blockIdx.x % kXcds;
+    const int k_item = a.p1_dynamic ? take_or_steal(a.queue + (kXcds + 1), a.p1_local, from_xcd) : (int)(blockIdx.x / kXcds);
+    if (k_item < 0) break;
+    int bid = xcd_work_item(a.p1_groups, a.p1_per_group, from_xcd, k_item);
+    if (bid < 0) continue;                                  // padding
     const int S = a.p1_splits, sp = bid % S; bid /= S;           // this wave's share of the key range
     const int g = bid % G; bid /= G;
     const int BKV = a.batch * a.kv_heads;
@@ -994,6 +1019,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         if (half == 0 && qi < a.n_pad) lse2[qi] = qi < N ? v : INFINITY;
         if (half == 0 && qi < N && lse_nat) lse_nat[qi] = v * 0.693147180559945309f;
     }
+    }   // next work item
 }
 
 int score_keys_per_block(int dtype_is_f32) { return 32 * (dtype_is_f32 ? Stream<float>::kSub : Stream<bf16_t>::kSub); }
@@ -1011,7 +1037,14 @@ static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
     a1.p1_splits = S;
     if (BKV >= kXcds) { a1.p1_groups = BKV; a1.p1_per_group = n_row_tiles * G * S; }
     else { a1.p1_groups = BKV * n_row_tiles; a1.p1_per_group = G * S; }
-    const unsigned grid1 = xcd_grid(a1.p1_groups, a1.p1_per_group);
+    // one queue per XCD; resident waves, one per SIMD (128 per XCD) at most.  The reset clears the
+    // second pass's cursors as well.
+    const long long per_xcd = xcd_grid(a1.p1_groups, a1.p1_per_group) / kXcds;
+    a1.p1_local = (int)per_xcd;
+    a1.p1_dynamic = per_xcd >= 4 * 128;                     // at least four rounds per resident wave
+    const unsigned grid1 = (unsigned)(kXcds * (a1.p1_dynamic ? 128 : per_xcd));
+    hipLaunchKernelGGL(score_queue_reset_kernel, dim3(1), dim3(64), 0, st, a.queue);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     hipLaunchKernelGGL((score_pass1_stream_kernel<T, D>), dim3(grid1), dim3(kWave), 0, st, a1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
