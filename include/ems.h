@@ -16,7 +16,9 @@
  *     caller.  The library never allocates, frees or synchronises: work is enqueued on
  *     the caller's stream (`hip_stream` is a hipStream_t, NULL = the default stream) and
  *     scratch space comes in through `ws` (sizes from ems_workspace_bytes; 256-byte
- *     aligned).  Outputs are fully overwritten.
+ *     aligned; its contents need no initialisation and mean nothing between calls).
+ *     ems_evict_merge_static is the one call without `ws`: it uses a fixed array that is
+ *     part of the loaded library.  Outputs are fully overwritten.
  *   - Layouts (Appendix A, "Two-Levels of Parallelism": (batch, heads, len, head_dim)):
  *         q        [B, Hq , N, D]      k, v     [B, Hkv, N, D]
  *     in `dtype` (bf16 or f32).  q-head h attends kv-head h / (Hq/Hkv).
