@@ -256,7 +256,6 @@ int ems_global_local_score(const ems_params* p, const void* q, const void* k,
     fill_score_args(a, p, plan, ws);
     const hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e = ems::launch_score_pass1(a, p->dtype == EMS_F32, st);
-    a.queue_clear = 1;                                      // the first pass cleared the second pass's cursors
     if (e == hipSuccess) e = ems::launch_score_pass2(a, p->dtype == EMS_F32, st);
     return e == hipSuccess ? EMS_OK : EMS_ERR_LAUNCH;
 }

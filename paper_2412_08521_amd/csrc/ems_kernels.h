@@ -161,7 +161,7 @@ constexpr int kDecodeMaxSlices = 32;     // row slices per head of the sliced de
 constexpr int kDecodeHandFloats = 384;   // floats of its per-head hand-over record
 bool decode_split(int budget, int n_imp, int n_tbm, int window, bool f32, int* slice_rows, int* n_slices);
 hipError_t launch_expand(const ExpandArgs& a, bool f32, hipStream_t st);
-hipError_t launch_score_pass1(const ScoreArgs& a, bool f32, hipStream_t st);   // rows' log-sum-exp
+hipError_t launch_score_pass1(ScoreArgs& a, bool f32, hipStream_t st);   // rows' log-sum-exp; sets a.queue_clear
 hipError_t launch_score_pass2(const ScoreArgs& a, bool f32, hipStream_t st);   // column sums
 hipError_t launch_select(const SelectArgs& a, hipStream_t st);
 hipError_t launch_evict_merge(const MergeArgs& a, bool f32, hipStream_t st);

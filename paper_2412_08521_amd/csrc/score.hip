@@ -1025,7 +1025,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 int score_keys_per_block(int dtype_is_f32) { return 32 * (dtype_is_f32 ? Stream<float>::kSub : Stream<bf16_t>::kSub); }
 
 template <typename T, int D>
-static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
+static hipError_t launch_pass1_t(ScoreArgs& a, hipStream_t st)
 {
     constexpr int kRows = 32 * Stream<T>::kSub;
     const int BKV = a.batch * a.kv_heads, G = a.q_heads / a.kv_heads;
@@ -1037,14 +1037,17 @@ static hipError_t launch_pass1_t(const ScoreArgs& a, hipStream_t st)
     a1.p1_splits = S;
     if (BKV >= kXcds) { a1.p1_groups = BKV; a1.p1_per_group = n_row_tiles * G * S; }
     else { a1.p1_groups = BKV * n_row_tiles; a1.p1_per_group = G * S; }
-    // one queue per XCD; resident waves, one per SIMD (128 per XCD) at most.  The reset clears the
-    // second pass's cursors as well.
+    // one queue per XCD; resident waves, one per SIMD (128 per XCD) at most.  The reset (long
+    // launches only: short ones do not use the cursors) clears the second pass's cursors as well.
     const long long per_xcd = xcd_grid(a1.p1_groups, a1.p1_per_group) / kXcds;
     a1.p1_local = (int)per_xcd;
     a1.p1_dynamic = per_xcd >= 4 * 128;                     // at least four rounds per resident wave
     const unsigned grid1 = (unsigned)(kXcds * (a1.p1_dynamic ? 128 : per_xcd));
-    hipLaunchKernelGGL(score_queue_reset_kernel, dim3(1), dim3(64), 0, st, a.queue);
-    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    a.queue_clear = a1.p1_dynamic;                          // tells a second pass that follows whether it still has to clear its cursors
+    if (a1.p1_dynamic) {
+        hipLaunchKernelGGL(score_queue_reset_kernel, dim3(1), dim3(64), 0, st, a.queue);
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    }
     hipLaunchKernelGGL((score_pass1_stream_kernel<T, D>), dim3(grid1), dim3(kWave), 0, st, a1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
@@ -1107,7 +1110,7 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
         return fn<bf16_t, 128>(a, st);                                       \
     } while (0)
 
-hipError_t launch_score_pass1(const ScoreArgs& a, bool f32, hipStream_t st) { EMS_DISPATCH(launch_pass1_t, a, f32, st); }
+hipError_t launch_score_pass1(ScoreArgs& a, bool f32, hipStream_t st) { EMS_DISPATCH(launch_pass1_t, a, f32, st); }
 hipError_t launch_score_pass2(const ScoreArgs& a, bool f32, hipStream_t st) { EMS_DISPATCH(launch_pass2_t, a, f32, st); }
 
 }  // namespace ems
