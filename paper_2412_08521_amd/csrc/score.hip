@@ -378,28 +378,39 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     // Long launches: a wave stays and takes item after item until the queues are empty -- the exit
     // every wave reaches (the cursors only grow); between two items nothing of the wave is in flight.
     // Short launches: one item per block.
+    // When the heads do not divide over the XCDs there are no queues: the groups (I, head) are
+    // dealt to the XCDs in turn and every block has one item, fixed by its index.
     for (bool first = true; first || a.q_dynamic; first = false) {
-    bool pool;
-    const int k = take_work_item(a.queue, a.p2_local, a.p2_pool, a.q_dynamic != 0, pool);
-    if (k < 0) break;
-    const int r_tiles = R / kKeys;
-    const int top = pool ? a.p2_split - 1 : n_chunks - 1;
-    const long long per = pool ? BKV : a.q_share;           // heads per chunk in this queue
-    const long long upto_top = p2_items_upto(top, r_tiles, n_key_tiles);
-    int lo = pool ? 0 : a.p2_split, hi = top;               // the chunk whose items include k: the smallest I with before(I) <= k
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (per * (upto_top - p2_items_upto(mid, r_tiles, n_key_tiles)) <= k) hi = mid; else lo = mid + 1;
+    int I, J, bkv;
+    if (a.q_share == 0) {
+        int bid = xcd_work_item(BKV * n_chunks, n_key_tiles, blockIdx.x % kXcds, blockIdx.x / kXcds);
+        if (bid < 0) break;
+        J = bid % n_key_tiles; bid /= n_key_tiles;
+        bkv = bid % BKV;
+        I = n_chunks - 1 - bid / BKV;
+    } else {
+        bool pool;
+        const int k = take_work_item(a.queue, a.p2_local, a.p2_pool, a.q_dynamic != 0, pool);
+        if (k < 0) break;
+        const int r_tiles = R / kKeys;
+        const int top = pool ? a.p2_split - 1 : n_chunks - 1;
+        const long long per = pool ? BKV : a.q_share;       // heads per chunk in this queue
+        const long long upto_top = p2_items_upto(top, r_tiles, n_key_tiles);
+        int lo = pool ? 0 : a.p2_split, hi = top;           // the chunk whose items include k: the smallest I with before(I) <= k
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (per * (upto_top - p2_items_upto(mid, r_tiles, n_key_tiles)) <= k) hi = mid; else lo = mid + 1;
+        }
+        I = lo;
+        const int rem = (int)(k - per * (upto_top - p2_items_upto(I, r_tiles, n_key_tiles)));
+        const int cnt = min(n_key_tiles, (I + 1) * r_tiles);
+        J = rem % cnt;
+        bkv = pool ? rem / cnt : (int)(blockIdx.x % kXcds) + kXcds * (rem / cnt);
     }
-    const int I = lo;
-    const int rem = (int)(k - per * (upto_top - p2_items_upto(I, r_tiles, n_key_tiles)));
-    const int cnt = min(n_key_tiles, (I + 1) * r_tiles);
-    const int J = rem % cnt;
-    const int bkv = pool ? rem / cnt : (int)(blockIdx.x % kXcds) + kXcds * (rem / cnt);
     const int key_base = J * kKeys;
     const int r_begin = max(I * R, key_base);               // both multiples of 32
     const int r_end = min((I + 1) * R, N);
-    if (r_begin >= r_end) continue;                         // (the queues hold no pair above the diagonal)
+    if (r_begin >= r_end) continue;                         // pair above the diagonal (the queues hold none)
     // [r_begin, e_end) touches the diagonal, [e_end, i_end) is interior, [i_end, r_end) holds
     // window rows (each range may be empty; all bounds but r_end are multiples of 32)
     const int win0 = N - W;
@@ -1066,8 +1077,8 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
         hipLaunchKernelGGL(lse_to_base2_kernel, g, dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     }
-    // Queues: an XCD queue per share of the heads when they divide over the XCDs, else one pool
-    // for everything.  With at least four rounds of items per resident wave (one wave per SIMD:
+    // Queues: an XCD queue per share of the heads when they divide over the XCDs (else no queues:
+    // groups dealt to the XCDs in turn, one block per pair).  With at least four rounds of items per resident wave (one wave per SIMD:
     // 128 per XCD) the waves stay and draw from the cursors, and the lightest row chunks -- about
     // 4.5 % of the items, which covers the spread between XCDs; more costs more in lost L2 sharing
     // than it balances -- go to the pool; shorter launches get one block per item.
@@ -1075,14 +1086,15 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
     const int r_tiles = a.chunk_rows / kKeys, top = a.n_chunks - 1;
     const long long all = p2_items_upto(top, r_tiles, n_key_tiles);
     a2.q_share = BKV % kXcds == 0 ? BKV / kXcds : 0;
-    a2.q_dynamic = (long long)BKV * all >= 4ll * 128 * kXcds;
-    a2.p2_split = a2.q_share ? 0 : a.n_chunks;
-    if (a2.q_share && a2.q_dynamic)
+    a2.q_dynamic = a2.q_share && (long long)BKV * all >= 4ll * 128 * kXcds;
+    a2.p2_split = 0;
+    if (a2.q_dynamic)
         while (a2.p2_split < top && p2_items_upto(a2.p2_split, r_tiles, n_key_tiles) <= all * 45 / 1000) ++a2.p2_split;
     const long long low = p2_items_upto(a2.p2_split - 1, r_tiles, n_key_tiles);
     const long long n_local = a2.q_share * (all - low), n_pool = (long long)BKV * low;
     const long long per_xcd = n_local + (n_pool + kXcds - 1) / kXcds;
-    const long long grid2 = kXcds * (a2.q_dynamic ? 128 : per_xcd);
+    const long long grid2 = !a2.q_share ? xcd_grid(BKV * a.n_chunks, n_key_tiles)     // no queues: a block per pair, padding included
+                                        : kXcds * (a2.q_dynamic ? 128 : per_xcd);
     if (a.chunk_rows % kKeys != 0 || grid2 > 0x7fffffffll) return hipErrorInvalidValue;
     a2.p2_local = (int)n_local; a2.p2_pool = (int)n_pool;
     if (a2.q_dynamic && !a.lse_in_nat && !a.queue_clear) {  // (the conversion kernel above, or the first pass's launch, cleared them already)

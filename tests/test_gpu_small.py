@@ -23,6 +23,7 @@ SCORE_SHAPES = [
     (1, 4, 1, 128, 300, 300),      # window == length
     (1, 8, 2, 128, 2500, 64),      # several row chunks in pass 2
     (1, 2, 2, 64, 4099, 70),       # window straddles a chunk boundary
+    (1, 6, 3, 128, 6000, 64),      # heads that do not divide over the XCDs: pairs dealt by block index
 ]
 
 
