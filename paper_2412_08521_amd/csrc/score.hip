@@ -117,9 +117,9 @@ __device__ __forceinline__ int xcd_work_item(int n_groups, int per_group, int xc
     const int group = (k / per_group) * kXcds + xcd;
     return group < n_groups ? group * per_group + k % per_group : -1;
 }
-static unsigned xcd_grid(int n_groups, int per_group)    // 8 x (items per XCD, padding included)
+static long long xcd_grid(long long n_groups, long long per_group)    // 8 x (items per XCD, padding included)
 {
-    return (unsigned)(kXcds * ((n_groups + kXcds - 1) / kXcds) * per_group);
+    return kXcds * ((n_groups + kXcds - 1) / kXcds) * per_group;
 }
 
 // ---- work queues.  The XCDs of one chip do not run at the same speed (a few percent apart under
@@ -1051,6 +1051,7 @@ static hipError_t launch_pass1_t(ScoreArgs& a, hipStream_t st)
     // one queue per XCD; resident waves, one per SIMD (128 per XCD) at most.  The reset (long
     // launches only: short ones do not use the cursors) clears the second pass's cursors as well.
     const long long per_xcd = xcd_grid(a1.p1_groups, a1.p1_per_group) / kXcds;
+    if (kXcds * per_xcd > 0x7fffffffll) return hipErrorInvalidValue;
     a1.p1_local = (int)per_xcd;
     a1.p1_dynamic = per_xcd >= 4 * 128;                     // at least four rounds per resident wave
     const unsigned grid1 = (unsigned)(kXcds * (a1.p1_dynamic ? 128 : per_xcd));
@@ -1093,8 +1094,9 @@ static hipError_t launch_pass2_t(const ScoreArgs& a, hipStream_t st)
     const long long low = p2_items_upto(a2.p2_split - 1, r_tiles, n_key_tiles);
     const long long n_local = a2.q_share * (all - low), n_pool = (long long)BKV * low;
     const long long per_xcd = n_local + (n_pool + kXcds - 1) / kXcds;
-    const long long grid2 = !a2.q_share ? xcd_grid(BKV * a.n_chunks, n_key_tiles)     // no queues: a block per pair, padding included
+    const long long grid2 = !a2.q_share ? xcd_grid((long long)BKV * a.n_chunks, n_key_tiles)     // no queues: a block per pair, padding included
                                         : kXcds * (a2.q_dynamic ? 128 : per_xcd);
+    if (n_local > 0x7fffffffll || n_pool > 0x7fffffffll) return hipErrorInvalidValue;
     if (a.chunk_rows % kKeys != 0 || grid2 > 0x7fffffffll) return hipErrorInvalidValue;
     a2.p2_local = (int)n_local; a2.p2_pool = (int)n_pool;
     if (a2.q_dynamic && !a.lse_in_nat && !a.queue_clear) {  // (the conversion kernel above, or the first pass's launch, cleared them already)
