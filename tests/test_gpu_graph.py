@@ -12,8 +12,11 @@ from paper_2412_08521_amd import binding as B
 pytestmark = pytest.mark.gpu
 
 
-def test_prefill_path_replays_bit_identically_from_a_graph():
-    b, hq, hkv, d, n, w, nb, r = 2, 4, 2, 128, 1500, 32, 160, 1.5
+# the second shape is long enough for the score passes to run as resident waves that draw their work
+# from queues (cursors cleared inside the recorded sequence) and for the chunked select
+@pytest.mark.parametrize("shape", [(2, 4, 2, 128, 1500, 32, 160, 1.5), (1, 32, 8, 64, 32768, 64, 256, 0.5)])
+def test_prefill_path_replays_bit_identically_from_a_graph(shape):
+    b, hq, hkv, d, n, w, nb, r = shape
     p = B.EmsParams(b, hq, hkv, d, n, w, nb, merge_ratio=r, tau=0.25, pool_kernel=7)
     n_imp, n_tbm = B.ems_partition_sizes(p)
     ws_bytes = B.ems_workspace_bytes(p)
