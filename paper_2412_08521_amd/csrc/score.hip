@@ -309,12 +309,67 @@ __global__ __launch_bounds__(256) void lse_to_base2_kernel(ScoreArgs a)
 //                  depend on each other) and between them the vector ALU turns the two
 //                  accumulators the previous pair left behind into weights; the next stage's
 //                  row operand and log-sum-exp are fetched from LDS into a second register set.
-// ------------------------------------------------------------------------------------
 // 32-wide subtiles of the stationary operand per wave (8 x 8 fragments = the 256 accumulation
 // registers in the 16-bit types) and LDS stages in the wave's ring
 template <typename T> struct Stream { static constexpr int kSub = 8; static constexpr int kRing = 4; };
 template <> struct Stream<float> { static constexpr int kSub = 2; static constexpr int kRing = 3; };
 constexpr int kStreamRows = 32;            // query rows per stage (one MFMA row tile)
+template <int v> using ic = std::integral_constant<int, v>;
+
+// The interior loops' DMA cursor, one step: source address `q` advances by a stage (kQStep bytes), at
+// the last stage of a head (h_left == 1 of per_head) by q_jump instead, and not at all once the
+// last stage of all is issued (t_left <= 1); `l` likewise with kLStep / l_jump.  Written out: left
+// to the compiler these few selects become several times as many instructions, part of them on
+// the vector ALU.
+template <int kQStep, int kLStep>
+__device__ __forceinline__ void advance_cursor(int& h_left, int& t_left, unsigned& q_lo, unsigned& q_hi, unsigned& l_lo,
+                                               unsigned& l_hi, int per_head, long long q_jump, long long l_jump)
+{
+    unsigned a0, a1, a2, a3;
+    asm volatile(
+        "s_cmp_eq_u32 %[h], 1\n\t"
+        "s_cselect_b32 %[a0], %[qj0], %[qs]\n\t"
+        "s_cselect_b32 %[a1], %[qj1], 0\n\t"
+        "s_cselect_b32 %[a2], %[lj0], %[ls]\n\t"
+        "s_cselect_b32 %[a3], %[lj1], 0\n\t"
+        "s_cselect_b32 %[h], %[ph], %[h]\n\t"
+        "s_sub_u32 %[h], %[h], 1\n\t"
+        "s_cmp_gt_i32 %[t], 1\n\t"
+        "s_cselect_b32 %[a0], %[a0], 0\n\t"
+        "s_cselect_b32 %[a1], %[a1], 0\n\t"
+        "s_cselect_b32 %[a2], %[a2], 0\n\t"
+        "s_cselect_b32 %[a3], %[a3], 0\n\t"
+        "s_sub_u32 %[t], %[t], 1\n\t"
+        "s_add_u32 %[q0], %[q0], %[a0]\n\t"
+        "s_addc_u32 %[q1], %[q1], %[a1]\n\t"
+        "s_add_u32 %[l0], %[l0], %[a2]\n\t"
+        "s_addc_u32 %[l1], %[l1], %[a3]"
+        : [h] "+s"(h_left), [t] "+s"(t_left), [q0] "+s"(q_lo), [q1] "+s"(q_hi), [l0] "+s"(l_lo), [l1] "+s"(l_hi),
+          [a0] "=&s"(a0), [a1] "=&s"(a1), [a2] "=&s"(a2), [a3] "=&s"(a3)
+        : [qj0] "s"((unsigned)q_jump), [qj1] "s"((unsigned)((unsigned long long)q_jump >> 32)),
+          [lj0] "s"((unsigned)l_jump), [lj1] "s"((unsigned)((unsigned long long)l_jump >> 32)),
+          [ph] "s"(per_head + 1), [qs] "i"(kQStep), [ls] "i"(kLStep)
+        : "scc");
+}
+
+// ------------------------------------------------------------------------------------
+
+// The same for one source without heads (the first pass's keys).
+template <int kStep>
+__device__ __forceinline__ void advance_cursor(int& t_left, unsigned& k_lo, unsigned& k_hi)
+{
+    unsigned a0;
+    asm volatile(
+        "s_cmp_gt_i32 %[t], 1\n\t"
+        "s_cselect_b32 %[a0], %[ks], 0\n\t"
+        "s_sub_u32 %[t], %[t], 1\n\t"
+        "s_add_u32 %[k0], %[k0], %[a0]\n\t"
+        "s_addc_u32 %[k1], %[k1], 0"
+        : [t] "+s"(t_left), [k0] "+s"(k_lo), [k1] "+s"(k_hi), [a0] "=&s"(a0)
+        : [ks] "i"(kStep)
+        : "scc");
+}
+
 
 // One 32-row x 32-key tile of the edge loop: weights added into the lane's column sums; the
 // tile may cross the diagonal and may hold last-window rows.
@@ -360,6 +415,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     static_assert((kRing - 1) * kLoads < 64, "vmcnt is a 6-bit counter");
     static_assert(kRing == 3 || kRing == 4, "the waits below are written for rings of 3 or 4 stages");
     constexpr int kKeys = 32 * kSub;
+    // stages per trip of the interior loop: after that many both the two operand register sets and
+    // the ring slots are back where they started, so every slot is a compile-time constant
+    constexpr int kUnroll = kRing % 2 ? 2 * kRing : kRing;
 
     __shared__ __attribute__((aligned(1024))) char lds_q[kRing][kStageBytes];
     __shared__ __attribute__((aligned(256))) float lds_lse[kRing][2 * kStreamRows];   // second half: spare
@@ -416,9 +474,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int win0 = N - W;
     int e_end = min(max(r_begin, min(key_base + kKeys, (win0 / kStreamRows) * kStreamRows)), r_end);
     const int i_end = min(max(e_end, (win0 / kStreamRows) * kStreamRows), r_end);
-    // the interior loop takes its stages in pairs: when their number is odd, one more row tile
-    // of every q-head is handled by the edge loop (which is correct for any row)
-    if ((((i_end - e_end) / kStreamRows) * G) & 1) e_end += kStreamRows;
+    // the interior loop takes kUnroll stages per trip: until their number divides, one more row
+    // tile of every q-head goes to the edge loop (which is correct for any row)
+    while ((((i_end - e_end) / kStreamRows) * G) % kUnroll) e_end += kStreamRows;
 
     const int b = bkv / a.kv_heads, kvh = bkv % a.kv_heads;
     const T* K = reinterpret_cast<const T*>(a.k) + ((size_t)bkv * N) * D;
@@ -564,50 +622,50 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     // wait count), so nothing in it can be moved out of the slot it was written in.
     if (e_end < i_end) {
         const int per_head = (i_end - e_end) / kStreamRows;
-        const int n_stages = per_head * G;                  // even
+        const int n_stages = per_head * G;                  // a multiple of kUnroll
 
         frag_t aq[2][kFrags];
         f32x16_t lse_v[2];
         f32x16_t acc[4];
-        // issue cursor of the next stage to fetch.  Where four DMA instructions go under one M0, the
-        // cursor is kept as running addresses (source rows, their log-sum-exp, the two ring slots)
-        // that advance by constants: a stage, or at the last stage of a q-head the jump to the next
-        // head's first interior row -- a handful of scalar instructions per stage.
+        // issue cursor of the next stage to fetch: countdowns of the stages it has left in its q-head
+        // and in all.  Where four DMA instructions go under one M0, the position is kept as running
+        // addresses (source rows, their log-sum-exp) that advance by a stage, at the last stage of
+        // a q-head by the jump to the next head's first interior row, and not at all once the last
+        // stage is issued -- masks instead of selects, a dozen scalar instructions per stage.
         constexpr bool kRunning = kKeepDmaOff && kQInstr % 4 == 0;
-        int u_next = 0, slot_next = 0, g_next = 0, row_next = e_end;
-        const char* q_src = reinterpret_cast<const char*>(Q0) + (size_t)e_end * kRowBytes;
-        const float* l_src = L0 + e_end;
-        unsigned dst_q = lds_q0, dst_l = lds_l0;
+        int h_left = per_head, t_left = n_stages;
+        int g_next = 0, row_next = e_end;
+        const unsigned long long q_first = reinterpret_cast<unsigned long long>(Q0) + (unsigned long long)e_end * kRowBytes;
+        const unsigned long long l_first = reinterpret_cast<unsigned long long>(L0 + e_end);
+        unsigned q_lo = (unsigned)q_first, q_hi = (unsigned)(q_first >> 32);
+        unsigned l_lo = (unsigned)l_first, l_hi = (unsigned)(l_first >> 32);
         const long long q_jump = ((long long)N - (i_end - e_end) + kStreamRows) * kRowBytes;   // last stage of a head -> next head
-        const long long l_jump = (long long)a.n_pad - (i_end - e_end) + kStreamRows;
+        const long long l_jump = ((long long)a.n_pad - (i_end - e_end) + kStreamRows) * 4;
         const unsigned lse_lane_off = (unsigned)col * 4u;
-        auto issue_next = [&]() __attribute__((always_inline)) {
+        auto issue_next = [&](auto slot_c) __attribute__((always_inline)) {
+            constexpr int slot = decltype(slot_c)::value;
             if constexpr (kRunning) {
+                const char* q_src = reinterpret_cast<const char*>(((unsigned long long)q_hi << 32) | q_lo);
+                const char* l_src = reinterpret_cast<const char*>(((unsigned long long)l_hi << 32) | l_lo);
 #pragma unroll
                 for (int j = 0; j < kQInstr; j += 4)
-                    dma_to_lds_x4(q_src + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst_q + j * 1024);
-                dma_to_lds<4>(l_src, lse_lane_off, dst_l);
+                    dma_to_lds_x4(q_src + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3],
+                                  lds_q0 + slot * kStageBytes + j * 1024);
+                dma_to_lds<4>(l_src, lse_lane_off, lds_l0 + slot * (2 * kStreamRows * 4));
+                advance_cursor<kStageBytes, kStreamRows * 4>(h_left, t_left, q_lo, q_hi, l_lo, l_hi, per_head, q_jump, l_jump);
             } else {
-                issue(g_next, row_next, slot_next, std::true_type{});
+                issue(g_next, row_next, slot, std::true_type{});
+                const bool wrap = h_left == 1, more = t_left > 1;
+                h_left = wrap ? per_head : h_left - 1;
+                --t_left;
+                g_next = more && wrap ? g_next + 1 : g_next;
+                row_next = more ? (wrap ? e_end : row_next + kStreamRows) : row_next;
             }
-            ++u_next;
-            const bool more = u_next < n_stages;            // else: stay on the last stage
-            const bool wrap = row_next + kStreamRows >= i_end;
-            const bool ring_wrap = slot_next + 1 == kRing;
-            slot_next = ring_wrap ? 0 : slot_next + 1;
-            if constexpr (kRunning) {
-                dst_q = ring_wrap ? lds_q0 : dst_q + kStageBytes;
-                dst_l = ring_wrap ? lds_l0 : dst_l + 2 * kStreamRows * 4;
-                q_src += more ? (wrap ? q_jump : (long long)kStreamRows * kRowBytes) : 0ll;
-                l_src += more ? (wrap ? l_jump : (long long)kStreamRows) : 0ll;
-            }
-            const int row_adv = wrap ? e_end : row_next + kStreamRows;
-            g_next = more && wrap ? g_next + 1 : g_next;
-            row_next = more ? row_adv : row_next;
         };
 
-#pragma unroll
-        for (int i = 0; i < kRing - 1; ++i) issue_next();
+        issue_next(ic<0>{});
+        issue_next(ic<1>{});
+        if constexpr (kRing > 3) issue_next(ic<2>{});
         wait_vmem<(kRing - 2) * kLoads>();
         fetch_rows(0, aq[0], lse_v[0]);
         // Pairs alternate between accumulators {0, 1} and {2, 3}.  The pipeline starts on a pair
@@ -623,10 +681,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         // previous pair (for p = 0 the last pair of the previous stage, whose rows' log-sum-exp is
         // in the other register set).  An accumulator is first read two MFMAs and a dozen vector
         // instructions after the chain that wrote it has ended.
-        auto stage = [&](int t, auto set_c) __attribute__((always_inline)) {
-            constexpr int set = decltype(set_c)::value;
+        auto stage = [&](auto u_c) __attribute__((always_inline)) {
+            constexpr int u = decltype(u_c)::value;         // stage t of the trip, t = u (mod kUnroll)
+            constexpr int set = u & 1;
             constexpr int kFetchAt = 1;                     // as early as the other register set is free: the LDS latency has three rounds to hide in
-            issue_next();                                   // stage t + kRing - 1
+            issue_next(ic<(u + kRing - 1) % kRing>{});      // stage t + kRing - 1
 #pragma unroll
             for (int p = 0; p < kPairs; ++p) {
                 constexpr int kOddPairs = kPairs % 2;
@@ -659,7 +718,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                     // after it are in flight.
                     if (kPairs > 1 && p == (kFetchAt < 1 ? 1 : kFetchAt) && f == 0) {
                         wait_vmem<(kRing - 2) * kLoads>();
-                        fetch_rows((t + 1) % kRing, aq[1 - set], lse_v[1 - set]);
+                        fetch_rows((u + 1) % kRing, aq[1 - set], lse_v[1 - set]);
                     }
                     // two rounds later those reads have long returned: one wait for all of them
                     if (kPairs > 2 && kFetchAt < kPairs - 1 && p == kPairs - 1 && f == 0) wait_lds_all_visible();
@@ -668,12 +727,18 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             }
             if (kPairs == 1) {                              // (validation type) nothing to hide the fetch behind
                 wait_vmem<(kRing - 2) * kLoads>();
-                fetch_rows((t + 1) % kRing, aq[1 - set], lse_v[1 - set]);
+                fetch_rows((u + 1) % kRing, aq[1 - set], lse_v[1 - set]);
             }
         };
-        for (int t = 0; t < n_stages; t += 2) {
-            stage(t, std::integral_constant<int, 0>{});
-            stage(t + 1, std::integral_constant<int, 1>{});
+        for (int t = 0; t < n_stages; t += kUnroll) {
+            stage(ic<0>{});
+            stage(ic<1>{});
+            stage(ic<2>{});
+            stage(ic<3>{});
+            if constexpr (kUnroll > 4) {
+                stage(ic<4>{});
+                stage(ic<5>{});
+            }
         }
         // the last pair (key subtiles kSub - 2 and kSub - 1 of the last stage, register set 1)
         {
@@ -743,6 +808,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     static_assert((kRing - 1) * kLoads < 64, "vmcnt is a 6-bit counter");
     static_assert(kRing == 3 || kRing == 4, "the waits below are written for rings of 3 or 4 stages");
     constexpr int kRows = 32 * kSub;                        // query rows per wave
+    // stages per trip of the interior loop (operand register sets and ring slots back at their start)
+    constexpr int kUnroll = kRing % 2 ? 2 * kRing : kRing;
 
     __shared__ __attribute__((aligned(1024))) char lds_k[kRing][kStageBytes];
 
@@ -854,12 +921,12 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int t_diag = max(t0, q_base / kStreamRows);
     const int n_edge = max(t1 - t_diag, 0);
     // interior stages [t0, min(t1, t_diag)): the first n_lead of them are done in the online form --
-    // one when there is no diagonal stage to take the reference from, one more to make the
-    // pipelined rest even
+    // one when there is no diagonal stage to take the reference from, more until the pipelined
+    // rest is whole trips of the loop
     const int n_int_all = max(min(t1, t_diag) - t0, 0);
     int n_lead = n_edge == 0 && n_int_all > 0 ? 1 : 0;
-    if ((n_int_all - n_lead) & 1) ++n_lead;
-    const int n_int = n_int_all - n_lead;                        // even, >= 0
+    n_lead = __builtin_amdgcn_readfirstlane(n_lead + (n_int_all - n_lead) % kUnroll);   // (wave-uniform; kept in a scalar register)
+    const int n_int = n_int_all - n_lead;                        // a multiple of kUnroll, >= 0
 
     float m_run[kSub], l_run[kSub];
 #pragma unroll
@@ -910,14 +977,29 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 #pragma unroll
             for (int e = 0; e < kEps; ++e) lsum[s][e] = 0.f;
 
-        int u_next = 0, slot_next = 0;
-        auto issue_next = [&]() __attribute__((always_inline)) {       // past the end: the last stage again, unread
-            issue(ti0 + min(u_next, n_int - 1), slot_next, std::true_type{});
-            ++u_next;
-            slot_next = slot_next + 1 == kRing ? 0 : slot_next + 1;
-        };
+        // issue cursor: where four DMA instructions go under one M0, a running source address
+        // that advances by a stage until the last stage is issued and then stays
+        constexpr bool kRunning = kKeepDmaOff && kLoads % 4 == 0;
+        int u_next = 0, t_left = n_int;
+        const unsigned long long k_first = reinterpret_cast<unsigned long long>(K) + (unsigned long long)ti0 * kStageBytes;
+        unsigned k_lo = (unsigned)k_first, k_hi = (unsigned)(k_first >> 32);
+        auto issue_next = [&](auto slot_c) __attribute__((always_inline)) {   // past the end: the last stage again, unread
+            constexpr int slot = decltype(slot_c)::value;
+            if constexpr (kRunning) {
+                const char* k_src = reinterpret_cast<const char*>(((unsigned long long)k_hi << 32) | k_lo);
 #pragma unroll
-        for (int i = 0; i < kRing - 1; ++i) issue_next();
+                for (int j = 0; j < kLoads; j += 4)
+                    dma_to_lds_x4(k_src + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3],
+                                  lds_k0 + slot * kStageBytes + j * 1024);
+                advance_cursor<kStageBytes>(t_left, k_lo, k_hi);
+            } else {
+                issue(ti0 + min(u_next, n_int - 1), slot, std::true_type{});
+                ++u_next;
+            }
+        };
+        issue_next(ic<0>{});
+        issue_next(ic<1>{});
+        if constexpr (kRing > 3) issue_next(ic<2>{});
         wait_vmem<(kRing - 2) * kLoads>();
         fetch_keys(0, ak[0]);
         // the pipeline starts on a pair that weighs nothing: exponents of -inf
@@ -927,9 +1009,10 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         // One stage = kPairs rounds; in round p the chains of query subtiles 2p and 2p+1 alternate
         // and after each MFMA the vector ALU weighs kEps elements of the matching tile of the
         // previous pair (same structure as the second pass; the exponent's offset is the lane's m).
-        auto stage = [&](int u, auto set_c) __attribute__((always_inline)) {
-            constexpr int set = decltype(set_c)::value;
-            issue_next();                                   // stage u + kRing - 1
+        auto stage = [&](auto u_c) __attribute__((always_inline)) {
+            constexpr int u = decltype(u_c)::value;         // the stage's place in the trip
+            constexpr int set = u & 1;
+            issue_next(ic<(u + kRing - 1) % kRing>{});      // the stage kRing - 1 ahead
 #pragma unroll
             for (int p = 0; p < kPairs; ++p) {
                 constexpr int kOddPairs = kPairs % 2;
@@ -966,9 +1049,15 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                 fetch_keys((u + 1) % kRing, ak[1 - set]);
             }
         };
-        for (int u = 0; u < n_int; u += 2) {
-            stage(u, std::integral_constant<int, 0>{});
-            stage(u + 1, std::integral_constant<int, 1>{});
+        for (int u0 = 0; u0 < n_int; u0 += kUnroll) {
+            stage(ic<0>{});
+            stage(ic<1>{});
+            stage(ic<2>{});
+            stage(ic<3>{});
+            if constexpr (kUnroll > 4) {
+                stage(ic<4>{});
+                stage(ic<5>{});
+            }
         }
         {   // the last pair (query subtiles kSub - 2 and kSub - 1 of the last stage, register set 1)
             constexpr int rp = ((kPairs % 2 ? 1 + kPairs - 1 : kPairs - 1)) & 1;
