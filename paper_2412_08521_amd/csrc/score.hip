@@ -51,7 +51,8 @@ __device__ __forceinline__ void dma_to_lds(const void* base, unsigned off, unsig
 // Four 16-byte DMA instructions under one M0 value: the instruction's immediate offset
 // (0, 1024, 2048, 3072) is added to the global address and to the LDS address alike, so
 // instruction i moves 1 KiB from base + off_i + 1024 i to LDS lds_addr + 1024 i.  The
-// per-lane offsets are passed without the 1024 i term.
+// per-lane offsets are passed without the 1024 i term; those of a stage's second (third, ..)
+// group of four hold the group's 4 KiB instead, so that all groups share one base.
 __device__ __forceinline__ void dma_to_lds_x4(const void* base, unsigned off0, unsigned off1, unsigned off2,
                                               unsigned off3, unsigned lds_addr)
 {
@@ -62,6 +63,26 @@ __device__ __forceinline__ void dma_to_lds_x4(const void* base, unsigned off0, u
                  "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
                  "global_load_lds_dwordx4 %3, %4 offset:3072"
                  ::"v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base), "s"(m0v) : "memory", "m0");
+}
+
+// The same two with the LDS address given as a wave-uniform base plus a compile-time offset: one
+// scalar instruction sets M0.
+template <int kLdsOff>
+__device__ __forceinline__ void dma_to_lds_x4_at(const void* base, unsigned off0, unsigned off1, unsigned off2,
+                                                 unsigned off3, unsigned lds_base)
+{
+    asm volatile("s_add_u32 m0, %5, %6\n\t"
+                 "global_load_lds_dwordx4 %0, %4\n\t"
+                 "global_load_lds_dwordx4 %1, %4 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
+                 "global_load_lds_dwordx4 %3, %4 offset:3072"
+                 ::"v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base), "s"(lds_base), "n"(kLdsOff) : "memory", "m0", "scc");
+}
+template <int kLdsOff>
+__device__ __forceinline__ void dma_dword_to_lds_at(const void* base, unsigned off, unsigned lds_base)
+{
+    asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base), "n"(kLdsOff)
+                 : "memory", "m0", "scc");
 }
 
 // The value itself, made opaque to the optimiser (stops loop-invariant code motion of what is
@@ -322,52 +343,40 @@ template <int v> using ic = std::integral_constant<int, v>;
 // to the compiler these few selects become several times as many instructions, part of them on
 // the vector ALU.
 template <int kQStep, int kLStep>
-__device__ __forceinline__ void advance_cursor(int& h_left, int& t_left, unsigned& q_lo, unsigned& q_hi, unsigned& l_lo,
-                                               unsigned& l_hi, int per_head, long long q_jump, long long l_jump)
+__device__ __forceinline__ void advance_cursor(int& h_left, int& t_left, const char*& q, const char*& l, int per_head,
+                                               long long q_jump, long long l_jump)
 {
-    unsigned a0, a1, a2, a3;
+    long long aq, al;
     asm volatile(
         "s_cmp_eq_u32 %[h], 1\n\t"
-        "s_cselect_b32 %[a0], %[qj0], %[qs]\n\t"
-        "s_cselect_b32 %[a1], %[qj1], 0\n\t"
-        "s_cselect_b32 %[a2], %[lj0], %[ls]\n\t"
-        "s_cselect_b32 %[a3], %[lj1], 0\n\t"
+        "s_cselect_b64 %[aq], %[qj], %[qs]\n\t"
+        "s_cselect_b64 %[al], %[lj], %[ls]\n\t"
         "s_cselect_b32 %[h], %[ph], %[h]\n\t"
         "s_sub_u32 %[h], %[h], 1\n\t"
         "s_cmp_gt_i32 %[t], 1\n\t"
-        "s_cselect_b32 %[a0], %[a0], 0\n\t"
-        "s_cselect_b32 %[a1], %[a1], 0\n\t"
-        "s_cselect_b32 %[a2], %[a2], 0\n\t"
-        "s_cselect_b32 %[a3], %[a3], 0\n\t"
-        "s_sub_u32 %[t], %[t], 1\n\t"
-        "s_add_u32 %[q0], %[q0], %[a0]\n\t"
-        "s_addc_u32 %[q1], %[q1], %[a1]\n\t"
-        "s_add_u32 %[l0], %[l0], %[a2]\n\t"
-        "s_addc_u32 %[l1], %[l1], %[a3]"
-        : [h] "+s"(h_left), [t] "+s"(t_left), [q0] "+s"(q_lo), [q1] "+s"(q_hi), [l0] "+s"(l_lo), [l1] "+s"(l_hi),
-          [a0] "=&s"(a0), [a1] "=&s"(a1), [a2] "=&s"(a2), [a3] "=&s"(a3)
-        : [qj0] "s"((unsigned)q_jump), [qj1] "s"((unsigned)((unsigned long long)q_jump >> 32)),
-          [lj0] "s"((unsigned)l_jump), [lj1] "s"((unsigned)((unsigned long long)l_jump >> 32)),
-          [ph] "s"(per_head + 1), [qs] "i"(kQStep), [ls] "i"(kLStep)
+        "s_cselect_b64 %[aq], %[aq], 0\n\t"
+        "s_cselect_b64 %[al], %[al], 0\n\t"
+        "s_sub_u32 %[t], %[t], 1"
+        : [h] "+s"(h_left), [t] "+s"(t_left), [aq] "=&s"(aq), [al] "=&s"(al)
+        : [qj] "s"(q_jump), [lj] "s"(l_jump), [ph] "s"(per_head + 1), [qs] "i"(kQStep), [ls] "i"(kLStep)
         : "scc");
+    q += aq;
+    l += al;
 }
-
-// ------------------------------------------------------------------------------------
 
 // The same for one source without heads (the first pass's keys).
 template <int kStep>
-__device__ __forceinline__ void advance_cursor(int& t_left, unsigned& k_lo, unsigned& k_hi)
+__device__ __forceinline__ void advance_cursor(int& t_left, const char*& k)
 {
-    unsigned a0;
+    long long ak;
     asm volatile(
         "s_cmp_gt_i32 %[t], 1\n\t"
-        "s_cselect_b32 %[a0], %[ks], 0\n\t"
-        "s_sub_u32 %[t], %[t], 1\n\t"
-        "s_add_u32 %[k0], %[k0], %[a0]\n\t"
-        "s_addc_u32 %[k1], %[k1], 0"
-        : [t] "+s"(t_left), [k0] "+s"(k_lo), [k1] "+s"(k_hi), [a0] "=&s"(a0)
+        "s_cselect_b64 %[ak], %[ks], 0\n\t"
+        "s_sub_u32 %[t], %[t], 1"
+        : [t] "+s"(t_left), [ak] "=&s"(ak)
         : [ks] "i"(kStep)
         : "scc");
+    k += ak;
 }
 
 
@@ -509,10 +518,10 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         const int slot = j * kWave + ln, row = slot / kCpr;
         return (unsigned)row * kRowBytes + (unsigned)(((slot % kCpr) ^ swz_key<T, D>(row)) << 4);
     };
-    unsigned dma_rel[kKeepDmaOff ? kQInstr : 1];            // the same, relative to the start of the instruction's 1 KiB
+    unsigned dma_rel[kKeepDmaOff ? kQInstr : 1];            // the same, less the offset the instruction itself adds (1 KiB x its place in a group of four)
     if (kKeepDmaOff) {
 #pragma unroll
-        for (int j = 0; j < kQInstr; ++j) dma_rel[j] = dma_src_off(j, lane) - (unsigned)j * 1024u;
+        for (int j = 0; j < kQInstr; ++j) dma_rel[j] = dma_src_off(j, lane) - (unsigned)(j % 4) * 1024u;
     }
     unsigned frag_off[kFrags];
 #pragma unroll
@@ -534,18 +543,18 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             if (kKeepDmaOff && kQInstr % 4 == 0) {
 #pragma unroll
                 for (int j = 0; j < kQInstr; j += 4)
-                    dma_to_lds_x4(base + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst + j * 1024);
+                    dma_to_lds_x4(base, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst + j * 1024);
             } else {
 #pragma unroll
                 for (int j = 0; j < kQInstr; ++j)
-                    dma_to_lds<16>(base, kKeepDmaOff ? dma_rel[j] + (unsigned)j * 1024u : dma_src_off(j, ln), dst + j * 1024);
+                    dma_to_lds<16>(base, kKeepDmaOff ? dma_rel[j] + (unsigned)(j % 4) * 1024u : dma_src_off(j, ln), dst + j * 1024);
             }
         } else {                                            // rows past the end re-read the last row
 #pragma unroll
             for (int j = 0; j < kQInstr; ++j) {
                 const int r = (j * kWave + lane) / kCpr;
                 const int over = max(row + r - (N - 1), 0);
-                const unsigned off = kKeepDmaOff ? dma_rel[j] + (unsigned)j * 1024u : dma_src_off(j, ln);
+                const unsigned off = kKeepDmaOff ? dma_rel[j] + (unsigned)(j % 4) * 1024u : dma_src_off(j, ln);
                 dma_to_lds<16>(qg, (unsigned)row * kRowBytes + off - (unsigned)over * kRowBytes, dst + j * 1024);
             }
         }
@@ -635,24 +644,22 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         constexpr bool kRunning = kKeepDmaOff && kQInstr % 4 == 0;
         int h_left = per_head, t_left = n_stages;
         int g_next = 0, row_next = e_end;
-        const unsigned long long q_first = reinterpret_cast<unsigned long long>(Q0) + (unsigned long long)e_end * kRowBytes;
-        const unsigned long long l_first = reinterpret_cast<unsigned long long>(L0 + e_end);
-        unsigned q_lo = (unsigned)q_first, q_hi = (unsigned)(q_first >> 32);
-        unsigned l_lo = (unsigned)l_first, l_hi = (unsigned)(l_first >> 32);
+        const char* q_src = reinterpret_cast<const char*>(Q0) + (size_t)e_end * kRowBytes;
+        const char* l_src = reinterpret_cast<const char*>(L0 + e_end);
         const long long q_jump = ((long long)N - (i_end - e_end) + kStreamRows) * kRowBytes;   // last stage of a head -> next head
         const long long l_jump = ((long long)a.n_pad - (i_end - e_end) + kStreamRows) * 4;
         const unsigned lse_lane_off = (unsigned)col * 4u;
+        const unsigned lds_q0s = __builtin_amdgcn_readfirstlane(lds_q0), lds_l0s = __builtin_amdgcn_readfirstlane(lds_l0);
         auto issue_next = [&](auto slot_c) __attribute__((always_inline)) {
             constexpr int slot = decltype(slot_c)::value;
             if constexpr (kRunning) {
-                const char* q_src = reinterpret_cast<const char*>(((unsigned long long)q_hi << 32) | q_lo);
-                const char* l_src = reinterpret_cast<const char*>(((unsigned long long)l_hi << 32) | l_lo);
-#pragma unroll
-                for (int j = 0; j < kQInstr; j += 4)
-                    dma_to_lds_x4(q_src + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3],
-                                  lds_q0 + slot * kStageBytes + j * 1024);
-                dma_to_lds<4>(l_src, lse_lane_off, lds_l0 + slot * (2 * kStreamRows * 4));
-                advance_cursor<kStageBytes, kStreamRows * 4>(h_left, t_left, q_lo, q_hi, l_lo, l_hi, per_head, q_jump, l_jump);
+                dma_to_lds_x4_at<slot * kStageBytes>(q_src, dma_rel[0], dma_rel[1], dma_rel[2], dma_rel[3], lds_q0s);
+                if constexpr (kQInstr > 4)
+                    dma_to_lds_x4_at<slot * kStageBytes + 4096>(q_src, dma_rel[4 % kQInstr], dma_rel[5 % kQInstr],
+                                                                dma_rel[6 % kQInstr], dma_rel[7 % kQInstr], lds_q0s);
+                static_assert(kQInstr <= 8 || !kRunning, "two groups of four per stage at most");
+                dma_dword_to_lds_at<slot * (2 * kStreamRows * 4)>(l_src, lse_lane_off, lds_l0s);
+                advance_cursor<kStageBytes, kStreamRows * 4>(h_left, t_left, q_src, l_src, per_head, q_jump, l_jump);
             } else {
                 issue(g_next, row_next, slot, std::true_type{});
                 const bool wrap = h_left == 1, more = t_left > 1;
@@ -681,6 +688,18 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         // previous pair (for p = 0 the last pair of the previous stage, whose rows' log-sum-exp is
         // in the other register set).  An accumulator is first read two MFMAs and a dozen vector
         // instructions after the chain that wrote it has ended.
+        // the vector ALU's share of one MFMA slot: kEps accumulator elements turned into weights and
+        // added to the column sums, written operation by operation so that no instruction follows
+        // the one it depends on (the scheduler keeps this order where it does not interleave itself)
+        auto weigh = [&](float (&sum)[kEps], const f32x16_t& s_acc, const f32x16_t& l, int f) __attribute__((always_inline)) {
+            float x[kEps];
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) x[e] = __builtin_fmaf(s_acc[f * kEps + e], c, -l[f * kEps + e]);
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) x[e] = exp2_fast(x[e]);
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) sum[e] += x[e];
+        };
         auto stage = [&](auto u_c) __attribute__((always_inline)) {
             constexpr int u = decltype(u_c)::value;         // stage t of the trip, t = u (mod kUnroll)
             constexpr int set = u & 1;
@@ -700,19 +719,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                 for (int f = 0; f < kFrags; ++f) {
                     if (f == 0) mma_first<T>(accA, aq[set][0], bk[2 * p][0]);
                     else mma<T>(accA, aq[set][f], bk[2 * p][f]);
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e) {
-                        const int r = f * kEps + e;
-                        part[psa][e] += exp2_fast(__builtin_fmaf(prevA[r], c, -pl[r]));
-                    }
+                    weigh(part[psa], prevA, pl, f);
                     __builtin_amdgcn_sched_barrier(0);
                     if (f == 0) mma_first<T>(accB, aq[set][0], bk[2 * p + 1][0]);
                     else mma<T>(accB, aq[set][f], bk[2 * p + 1][f]);
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e) {
-                        const int r = f * kEps + e;
-                        part[psa + 1][e] += exp2_fast(__builtin_fmaf(prevB[r], c, -pl[r]));
-                    }
+                    weigh(part[psa + 1], prevB, pl, f);
                     // The other register set is free once round 0 has read the previous stage's
                     // log-sum-exp; stage t + 1 has landed once only the kRing - 2 stages issued
                     // after it are in flight.
@@ -865,7 +876,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     unsigned dma_rel[kKeepDmaOff ? kLoads : 1];
     if (kKeepDmaOff) {
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) { dma_off[j] = dma_src_off(j, lane); dma_rel[j] = dma_off[j] - (unsigned)j * 1024u; }
+        for (int j = 0; j < kLoads; ++j) { dma_off[j] = dma_src_off(j, lane); dma_rel[j] = dma_off[j] - (unsigned)(j % 4) * 1024u; }
     }
     unsigned frag_off[kFrags];
 #pragma unroll
@@ -885,7 +896,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             if (kKeepDmaOff && kLoads % 4 == 0) {
 #pragma unroll
                 for (int j = 0; j < kLoads; j += 4)
-                    dma_to_lds_x4(base + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst + j * 1024);
+                    dma_to_lds_x4(base, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3], dst + j * 1024);
             } else {
 #pragma unroll
                 for (int j = 0; j < kLoads; ++j)
@@ -981,17 +992,17 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         // that advances by a stage until the last stage is issued and then stays
         constexpr bool kRunning = kKeepDmaOff && kLoads % 4 == 0;
         int u_next = 0, t_left = n_int;
-        const unsigned long long k_first = reinterpret_cast<unsigned long long>(K) + (unsigned long long)ti0 * kStageBytes;
-        unsigned k_lo = (unsigned)k_first, k_hi = (unsigned)(k_first >> 32);
+        const char* k_src = reinterpret_cast<const char*>(K) + (size_t)ti0 * kStageBytes;
+        const unsigned lds_k0s = __builtin_amdgcn_readfirstlane(lds_k0);
         auto issue_next = [&](auto slot_c) __attribute__((always_inline)) {   // past the end: the last stage again, unread
             constexpr int slot = decltype(slot_c)::value;
             if constexpr (kRunning) {
-                const char* k_src = reinterpret_cast<const char*>(((unsigned long long)k_hi << 32) | k_lo);
-#pragma unroll
-                for (int j = 0; j < kLoads; j += 4)
-                    dma_to_lds_x4(k_src + j * 1024, dma_rel[j], dma_rel[j + 1], dma_rel[j + 2], dma_rel[j + 3],
-                                  lds_k0 + slot * kStageBytes + j * 1024);
-                advance_cursor<kStageBytes>(t_left, k_lo, k_hi);
+                dma_to_lds_x4_at<slot * kStageBytes>(k_src, dma_rel[0], dma_rel[1], dma_rel[2], dma_rel[3], lds_k0s);
+                if constexpr (kLoads > 4)
+                    dma_to_lds_x4_at<slot * kStageBytes + 4096>(k_src, dma_rel[4 % kLoads], dma_rel[5 % kLoads],
+                                                                dma_rel[6 % kLoads], dma_rel[7 % kLoads], lds_k0s);
+                static_assert(kLoads <= 8 || !kRunning, "two groups of four per stage at most");
+                advance_cursor<kStageBytes>(t_left, k_src);
             } else {
                 issue(ti0 + min(u_next, n_int - 1), slot, std::true_type{});
                 ++u_next;
@@ -1009,6 +1020,17 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         // One stage = kPairs rounds; in round p the chains of query subtiles 2p and 2p+1 alternate
         // and after each MFMA the vector ALU weighs kEps elements of the matching tile of the
         // previous pair (same structure as the second pass; the exponent's offset is the lane's m).
+        // the vector ALU's share of one MFMA slot, operation by operation (no instruction follows
+        // the one it depends on)
+        auto weigh = [&](float (&sum)[kEps], const f32x16_t& s_acc, float m, int f) __attribute__((always_inline)) {
+            float x[kEps];
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) x[e] = __builtin_fmaf(s_acc[f * kEps + e], c, -m);
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) x[e] = exp2_fast(x[e]);
+#pragma unroll
+            for (int e = 0; e < kEps; ++e) sum[e] += x[e];
+        };
         auto stage = [&](auto u_c) __attribute__((always_inline)) {
             constexpr int u = decltype(u_c)::value;         // the stage's place in the trip
             constexpr int set = u & 1;
@@ -1026,15 +1048,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                 for (int f = 0; f < kFrags; ++f) {
                     if (f == 0) mma_first<T>(accA, ak[set][0], bq[2 * p][0]);
                     else mma<T>(accA, ak[set][f], bq[2 * p][f]);
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e)
-                        lsum[psa][e] += exp2_fast(__builtin_fmaf(prevA[f * kEps + e], c, -m_fix[psa]));
+                    weigh(lsum[psa], prevA, m_fix[psa], f);
                     __builtin_amdgcn_sched_barrier(0);
                     if (f == 0) mma_first<T>(accB, ak[set][0], bq[2 * p + 1][0]);
                     else mma<T>(accB, ak[set][f], bq[2 * p + 1][f]);
-#pragma unroll
-                    for (int e = 0; e < kEps; ++e)
-                        lsum[psa + 1][e] += exp2_fast(__builtin_fmaf(prevB[f * kEps + e], c, -m_fix[psa + 1]));
+                    weigh(lsum[psa + 1], prevB, m_fix[psa + 1], f);
                     if (kPairs > 1 && p == 1 && f == 0) {   // the other register set is free; early, so that the LDS latency hides
                         wait_vmem<(kRing - 2) * kLoads>();
                         fetch_keys((u + 1) % kRing, ak[1 - set]);
