@@ -52,6 +52,26 @@ def test_score_matches_oracle(shape, mode):
     np.testing.assert_allclose(s_loc.sum(-1).cpu().numpy(), G * w, rtol=1e-4)
 
 
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("group", [1, 2, 3, 4])
+def test_score_every_remainder_of_interior_stages(group, mode):
+    """The pipelined loops of both passes take whole trips of 4 stages (6 in f32 mode); what does not fill
+    a trip goes through the masked loop.  Lengths 32 apart walk through every remainder, for every group size
+    (the trip counts stages of all q-heads of a group), plus one ragged length."""
+    lengths = [1312 + 32 * i for i in range(6 if mode == B.EMS_F32 else 4)] + [1333]
+    for d in ([64, 128] if group in (1, 3) else [64]):
+        for n in lengths:
+            _log("score remainders: group", group, "d", d, "n", n, "mode", mode)
+            inp = ems_inputs.small(1, group, 1, d, n, seed=n + group)
+            p = B.EmsParams(1, group, 1, d, n, 32, dtype=mode)
+            s_glo, s_loc, lse = B.ems_global_local_score(p, dev_tensor(inp.q, mode), dev_tensor(inp.k, mode), want_lse=True)
+            torch.cuda.synchronize()
+            o_glo, o_loc, o_lse = ems_ref.score(ref_params(p), inp.f32("q"), inp.f32("k"), want_lse=True)
+            assert_rel(s_glo.cpu().numpy(), o_glo, RTOL[mode], f"s_glo n={n} d={d}")
+            assert_rel(s_loc.cpu().numpy(), o_loc, RTOL[mode], f"s_loc n={n} d={d}")
+            np.testing.assert_allclose(lse.cpu().numpy(), o_lse, rtol=0, atol=2e-5 if mode == B.EMS_F32 else 2e-2)
+
+
 def test_score_custom_scale_and_large_logits():
     """Logits of magnitude ~40: the running maximum of pass 1 has to do its job."""
     b, hq, hkv, d, n, w = 1, 2, 2, 128, 600, 16
