@@ -872,11 +872,10 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         const int slot = j * kWave + ln, row = slot / kCpr;
         return (unsigned)row * kRowBytes + (unsigned)(((slot % kCpr) ^ swz_key<T, D>(row)) << 4);
     };
-    unsigned dma_off[kKeepDmaOff ? kLoads : 1];
-    unsigned dma_rel[kKeepDmaOff ? kLoads : 1];
+    unsigned dma_rel[kKeepDmaOff ? kLoads : 1];             // less the offset the instruction itself adds (1 KiB x its place in a group of four)
     if (kKeepDmaOff) {
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) { dma_off[j] = dma_src_off(j, lane); dma_rel[j] = dma_off[j] - (unsigned)(j % 4) * 1024u; }
+        for (int j = 0; j < kLoads; ++j) dma_rel[j] = dma_src_off(j, lane) - (unsigned)(j % 4) * 1024u;
     }
     unsigned frag_off[kFrags];
 #pragma unroll
@@ -900,14 +899,14 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             } else {
 #pragma unroll
                 for (int j = 0; j < kLoads; ++j)
-                    dma_to_lds<16>(base, kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln), dst + j * 1024);
+                    dma_to_lds<16>(base, kKeepDmaOff ? dma_rel[j] + (unsigned)(j % 4) * 1024u : dma_src_off(j, ln), dst + j * 1024);
             }
         } else {                                            // keys past the end re-read the last key (always masked)
 #pragma unroll
             for (int j = 0; j < kLoads; ++j) {
                 const int r = (j * kWave + lane) / kCpr;
                 const int over = max(row + r - (N - 1), 0);
-                const unsigned off = kKeepDmaOff ? dma_off[j] : dma_src_off(j, ln);
+                const unsigned off = kKeepDmaOff ? dma_rel[j] + (unsigned)(j % 4) * 1024u : dma_src_off(j, ln);
                 dma_to_lds<16>(K, (unsigned)row * kRowBytes + off - (unsigned)over * kRowBytes, dst + j * 1024);
             }
         }
